@@ -1,0 +1,148 @@
+"""Plain definitions of the two tensor-parallel results, in float64.
+
+Test infrastructure only (see the package docstring).
+
+Notation follows the paper (section 4, experimental setup; figures "AG + GEMM"
+and "GEMM + RS"): P ranks, a global GEMM M x N x K with A of shape M x K and B
+of shape K x N, both row-major.
+
+GEMM + reduce-scatter (sections 3.1.3 and 4.1).  Rank r holds the K-slice
+K_r = [r*K/P, (r+1)*K/P): A_local = A[:, K_r] (M x K/P) and B_local = B[K_r, :]
+(K/P x N).  Its local product own = A_local . B_local is a full M x N matrix of
+partial sums; the rows R_q = [q*M/P, (q+1)*M/P) of it belong to rank q.  The
+result rank r ends up with is its shard of the reduced matrix,
+    out[i', j] = sum_{p<P} (A[:, K_p] . B[K_p, :])[r*M/P + i', j].
+The method only overlaps the exchange with the GEMM; it reaches exactly this
+sum (up to rounding order), so the oracle is the sum written out.
+
+All-gather + GEMM (section 4.1).  Rank r holds row-chunk r of A (M/P x K) and
+the column slice B[:, N_r] (K x N/P); after the gather it computes
+    C[:, N_r] = A . B[:, N_r]                       (M x N/P).
+The order in which chunks arrive does not enter the definition.
+
+Readings where the paper is silent (the 8-bit path is an extension):
+  * the scattered output dimension is the row dimension M;
+  * cross-rank sums are taken over float32 per-source partial slots (the
+    oracle adds them in float64, slot order 0..P-1);
+  * 8-bit inputs carry one float32 scale per tensor; the unscaled products are
+    accumulated and the product of the two scales is applied once at the end.
+"""
+import numpy as np
+
+from . import codec
+
+
+def _scale(scale_a, scale_b):
+    sa = 1.0 if scale_a is None else float(np.float32(scale_a))
+    sb = 1.0 if scale_b is None else float(np.float32(scale_b))
+    return sa * sb
+
+
+def local_product(a_bits, b_bits, dtype, scale_a=None, scale_b=None, rows=None):
+    """(scale_a*scale_b) * A . B in float64 from the stored bit patterns.
+
+    a_bits: m x k, b_bits: k x n.  rows (optional index array) restricts the
+    result to those rows of A: the returned array is len(rows) x n.
+    """
+    a_bits = np.asarray(a_bits)
+    b_bits = np.asarray(b_bits)
+    if a_bits.ndim != 2 or b_bits.ndim != 2 or a_bits.shape[1] != b_bits.shape[0]:
+        raise ValueError(f"shape mismatch {a_bits.shape} x {b_bits.shape}")
+    if rows is not None:
+        a_bits = a_bits[np.asarray(rows, dtype=np.int64)]
+    a = codec.decode(a_bits, dtype)
+    b = codec.decode(b_bits, dtype)
+    return _scale(scale_a, scale_b) * (a @ b)
+
+
+def gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials,
+            scale_a=None, scale_b=None):
+    """One rank's GEMM + reduce-scatter.
+
+    a_local_bits: M x K/P, b_local_bits: K/P x N.
+    partials:     [P][M/P][N] float32; slot q (q != rank) is what rank q sent for
+                  this rank's shard.  Slot `rank` is ignored.
+    Returns a dict:
+      own       M x N float64, this rank's local product;
+      outgoing  [P][M/P][N] float64, slot q = rows R_q of own (what is sent to
+                rank q; slot `rank` is this rank's own contribution);
+      out       M/P x N float64, the reduced shard, not rounded;
+      out_bf16  the same rounded once to bf16 (as uint16 bit patterns).
+    """
+    own = local_product(a_local_bits, b_local_bits, dtype, scale_a, scale_b)
+    M, N = own.shape
+    if M % P:
+        raise ValueError("M must be a multiple of P")
+    mp = M // P
+    partials = np.asarray(partials)
+    if partials.shape != (P, mp, N):
+        raise ValueError(f"partials shape {partials.shape} != {(P, mp, N)}")
+    outgoing = own.reshape(P, mp, N)
+    out = np.zeros((mp, N), dtype=np.float64)
+    for p in range(P):
+        out += outgoing[rank] if p == rank else partials[p].astype(np.float64)
+    return {"own": own, "outgoing": outgoing, "out": out,
+            "out_bf16": codec.bf16_encode(out)}
+
+
+def gemm_rs_rows(P, rank, a_local_bits, b_local_bits, dtype, partials, rows,
+                 scale_a=None, scale_b=None):
+    """The same result restricted to the global rows `rows` of the local product.
+
+    Returns (own_rows, out_rows): own_rows is len(rows) x N float64; out_rows has
+    the reduced value for rows that fall in this rank's shard R_rank and NaN
+    rows elsewhere.
+    """
+    rows = np.asarray(rows, dtype=np.int64)
+    own_rows = local_product(a_local_bits, b_local_bits, dtype, scale_a, scale_b, rows=rows)
+    M = np.asarray(a_local_bits).shape[0]
+    mp = M // P
+    out_rows = np.full_like(own_rows, np.nan)
+    for t, i in enumerate(rows):
+        if i // mp != rank:
+            continue
+        acc = np.zeros(own_rows.shape[1], dtype=np.float64)
+        for p in range(P):
+            acc += own_rows[t] if p == rank else np.asarray(partials[p][i - rank * mp], dtype=np.float64)
+        out_rows[t] = acc
+    return own_rows, out_rows
+
+
+def reduce_partials(partials):
+    """Sum of the P float32 partial slots, slot order 0..P-1, in float64: [M/P][N]."""
+    partials = np.asarray(partials)
+    out = np.zeros(partials.shape[1:], dtype=np.float64)
+    for p in range(partials.shape[0]):
+        out += partials[p].astype(np.float64)
+    return out
+
+
+def gather_chunks(chunks):
+    """A_gathered = the P row-chunks stacked in rank order (chunk q = rows R_q)."""
+    return np.concatenate([np.asarray(c) for c in chunks], axis=0)
+
+
+def ag_gemm(P, rank, a_gathered_bits, b_local_bits, dtype,
+            scale_a=None, scale_b=None, rows=None):
+    """One rank's all-gather + GEMM: C[:, N_rank] = A . B[:, N_rank].
+
+    a_gathered_bits: M x K (all P chunks in place), b_local_bits: K x N/P.
+    Returns a dict: C (M x N/P float64, or len(rows) x N/P), C_bf16 (uint16).
+    """
+    M = np.asarray(a_gathered_bits).shape[0]
+    if M % P:
+        raise ValueError("M must be a multiple of P")
+    if not 0 <= rank < P:
+        raise ValueError("rank out of range")
+    c = local_product(a_gathered_bits, b_local_bits, dtype, scale_a, scale_b, rows=rows)
+    return {"C": c, "C_bf16": codec.bf16_encode(c)}
+
+
+def abs_product(a_bits, b_bits, dtype, scale_a=None, scale_b=None, rows=None):
+    """|scale| * |A| . |B|: the magnitude sum that bounds float32 accumulation error."""
+    a_bits = np.asarray(a_bits)
+    if rows is not None:
+        a_bits = a_bits[np.asarray(rows, dtype=np.int64)]
+    a = np.abs(codec.decode(a_bits, dtype))
+    b = np.abs(codec.decode(np.asarray(b_bits), dtype))
+    return abs(_scale(scale_a, scale_b)) * (a @ b)

@@ -1,0 +1,217 @@
+"""Pins for the oracle's GEMM+RS / AG+GEMM definitions: exact integer and rational
+brute force, textbook special cases, the linearity and shard-concatenation
+identities.  None of the expected values below is produced by the oracle."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import codec, tp_gemm
+from paper_2511_13940_amd import workloads as wl
+
+
+def _int_bits(x, dtype):
+    """Small integers are exact in both storage formats."""
+    if dtype == "bf16":
+        return wl.to_bf16_bits(x.astype(np.float32))
+    import torch
+    return torch.from_numpy(x.astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+def _brute_int(a, b):
+    """Triple loop in Python integers."""
+    m, k = a.shape
+    n = b.shape[1]
+    return [[sum(int(a[i, t]) * int(b[t, j]) for t in range(k)) for j in range(n)] for i in range(m)]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+@pytest.mark.parametrize("m,n,k", [(1, 1, 1), (2, 3, 5), (7, 5, 3), (17, 13, 11), (4, 9, 16)])
+def test_local_product_integer_brute_force(dtype, m, n, k):
+    a = wl.small_int_matrix((m, k), 11, m * 100 + k)
+    b = wl.small_int_matrix((k, n), 12, n * 100 + k)
+    got = tp_gemm.local_product(_int_bits(a, dtype), _int_bits(b, dtype), dtype)
+    assert got.shape == (m, n)
+    assert np.array_equal(got, np.array(_brute_int(a, b), dtype=np.float64))
+
+
+def test_local_product_rational_brute_force_bf16():
+    """Random bf16 inputs, exact rational dot products; float64 accumulation of 11 terms
+    is within a few ulp of the exact value."""
+    m, n, k = 5, 7, 11
+    rng = np.random.default_rng(5)
+    a_bits = wl.to_bf16_bits(rng.standard_normal((m, k)).astype(np.float32))
+    b_bits = wl.to_bf16_bits(rng.standard_normal((k, n)).astype(np.float32))
+    af = [[Fraction(float(v)) for v in row] for row in codec.bf16_decode(a_bits)]
+    bf = [[Fraction(float(v)) for v in row] for row in codec.bf16_decode(b_bits)]
+    got = tp_gemm.local_product(a_bits, b_bits, "bf16")
+    for i in range(m):
+        for j in range(n):
+            exact = sum(af[i][t] * bf[t][j] for t in range(k))
+            mag = sum(abs(af[i][t] * bf[t][j]) for t in range(k))
+            assert abs(Fraction(float(got[i, j])) - exact) <= mag * Fraction(k, 2 ** 52)
+
+
+def test_local_product_special_cases():
+    rng = np.random.default_rng(9)
+    a = rng.integers(-3, 4, size=(6, 6)).astype(np.float32)
+    eye = np.eye(6, dtype=np.float32)
+    perm = eye[:, [2, 0, 5, 1, 4, 3]]
+    ab = wl.to_bf16_bits(a)
+    assert np.array_equal(tp_gemm.local_product(ab, wl.to_bf16_bits(eye), "bf16"), a)
+    assert np.array_equal(tp_gemm.local_product(wl.to_bf16_bits(eye), ab, "bf16"), a)
+    # A.Perm permutes columns, Perm.A permutes rows: catches a transposed operand
+    assert np.array_equal(tp_gemm.local_product(ab, wl.to_bf16_bits(perm), "bf16"), a[:, [2, 0, 5, 1, 4, 3]])
+    assert np.array_equal(tp_gemm.local_product(wl.to_bf16_bits(perm.T), ab, "bf16"), a[[2, 0, 5, 1, 4, 3], :])
+    ones = np.ones((6, 4), dtype=np.float32)
+    assert np.array_equal(tp_gemm.local_product(ab, wl.to_bf16_bits(ones), "bf16"),
+                          np.repeat(a.sum(axis=1, keepdims=True), 4, axis=1))
+
+
+def test_scales_are_applied_once_fp8():
+    a = wl.small_int_matrix((3, 8), 1, 1)
+    b = wl.small_int_matrix((8, 5), 1, 2)
+    sa, sb = np.float32(0.25), np.float32(8.0)
+    got = tp_gemm.local_product(_int_bits(a, "fp8"), _int_bits(b, "fp8"), "fp8", sa, sb)
+    assert np.array_equal(got, 2.0 * np.array(_brute_int(a, b), dtype=np.float64))
+    sa, sb = np.float32(0.1), np.float32(0.3)   # not exactly representable: taken as float32 values
+    got = tp_gemm.local_product(_int_bits(a, "fp8"), _int_bits(b, "fp8"), "fp8", sa, sb)
+    s = Fraction(float(sa)) * Fraction(float(sb))
+    ref = np.array([[float(s * v) for v in row] for row in _brute_int(a, b)])
+    assert np.allclose(got, ref, rtol=1e-15, atol=0)
+
+
+@pytest.mark.parametrize("P,M,N,K", [(2, 4, 3, 6), (3, 6, 5, 9), (4, 8, 2, 8)])
+def test_gemm_rs_integer_brute_force_all_ranks(P, M, N, K):
+    """Every rank run on one global integer problem with true partials: each reduced
+    shard equals the rows of the unsharded product, and the outgoing slots are the
+    right row blocks of the local product."""
+    A = wl.small_int_matrix((M, K), 21, 1)
+    B = wl.small_int_matrix((K, N), 21, 2)
+    full = np.array(_brute_int(A, B), dtype=np.float64)
+    kp, mp = K // P, M // P
+    local = [np.array(_brute_int(A[:, r * kp:(r + 1) * kp], B[r * kp:(r + 1) * kp, :]), dtype=np.float64)
+             for r in range(P)]
+    assert np.array_equal(sum(local), full)                       # linearity, in integers
+    for r in range(P):
+        partials = np.zeros((P, mp, N), dtype=np.float32)
+        for q in range(P):
+            if q != r:
+                partials[q] = local[q][r * mp:(r + 1) * mp]
+        partials[r] = 12345.0                                      # must be ignored
+        res = tp_gemm.gemm_rs(P, r, _int_bits(A[:, r * kp:(r + 1) * kp], "bf16"),
+                              _int_bits(B[r * kp:(r + 1) * kp, :], "bf16"), "bf16", partials)
+        assert np.array_equal(res["own"], local[r])
+        for q in range(P):
+            assert np.array_equal(res["outgoing"][q], local[r][q * mp:(q + 1) * mp])
+        assert np.array_equal(res["out"], full[r * mp:(r + 1) * mp])
+        assert np.array_equal(codec.bf16_decode(res["out_bf16"]), full[r * mp:(r + 1) * mp])
+
+
+def test_linearity_and_shard_concatenation_random_bf16():
+    """Sum over ranks of A[:,K_p].B[K_p,:] equals the unsharded GEMM (to float64 rounding),
+    and the P reduced shards stacked give the whole product."""
+    P, M, N, K = 4, 16, 12, 64
+    g = wl.global_problem(M, N, K, "bf16", seed=3)
+    A = codec.bf16_decode(g["A"])
+    B = codec.bf16_decode(g["B"])
+    full = np.zeros((M, N))
+    for i in range(M):                        # independent plain evaluation, k ascending
+        for j in range(N):
+            s = 0.0
+            for t in range(K):
+                s += A[i, t] * B[t, j]
+            full[i, j] = s
+    mp = M // P
+    shares = [wl.slice_gemm_rs(g, P, r) for r in range(P)]
+    owns = [tp_gemm.local_product(a, b, "bf16") for a, b in shares]
+    assert np.allclose(sum(owns), full, rtol=0, atol=K * 2.0 ** -52)
+    shards = []
+    for r in range(P):
+        partials = np.zeros((P, mp, N), dtype=np.float32)
+        for q in range(P):
+            if q != r:
+                partials[q] = owns[q][r * mp:(r + 1) * mp].astype(np.float32)
+        shards.append(tp_gemm.gemm_rs(P, r, shares[r][0], shares[r][1], "bf16", partials)["out"])
+    stacked = np.concatenate(shards, axis=0)
+    # peers' contributions were rounded to float32 on the way: 3 roundings of ~|x|*2^-24 each
+    assert np.allclose(stacked, full, rtol=0, atol=4 * 2.0 ** -24)
+
+
+def test_ag_gemm_concatenation_and_chunk_order():
+    P, M, N, K = 4, 8, 12, 10
+    A = wl.small_int_matrix((M, K), 31, 1)
+    B = wl.small_int_matrix((K, N), 31, 2)
+    full = np.array(_brute_int(A, B), dtype=np.float64)
+    g = {"A": _int_bits(A, "bf16"), "B": _int_bits(B, "bf16")}
+    chunks = [wl.slice_ag_gemm(g, P, q)[0] for q in range(P)]
+    gathered = tp_gemm.gather_chunks(chunks)
+    assert np.array_equal(gathered, g["A"])                       # A_gathered == concat of the chunks
+    cols = []
+    for r in range(P):
+        _, b_loc = wl.slice_ag_gemm(g, P, r)
+        res = tp_gemm.ag_gemm(P, r, gathered, b_loc, "bf16")
+        assert res["C"].shape == (M, N // P)
+        cols.append(res["C"])
+    assert np.array_equal(np.concatenate(cols, axis=1), full)
+    sub = tp_gemm.ag_gemm(P, 1, gathered, wl.slice_ag_gemm(g, P, 1)[1], "bf16", rows=[5, 0])
+    assert np.array_equal(sub["C"], full[[5, 0], 3:6])
+
+
+def test_reduce_closed_forms():
+    P, mp, N = 5, 3, 4
+    consts = np.array([1.5, -2.25, 4.0, 0.125, 7.0], dtype=np.float32)
+    partials = np.broadcast_to(consts[:, None, None], (P, mp, N)).copy()
+    assert np.array_equal(tp_gemm.reduce_partials(partials), np.full((mp, N), consts.astype(np.float64).sum()))
+    x = np.random.default_rng(2).standard_normal((mp, N)).astype(np.float32)
+    pm = np.stack([x, -x, 2 * x, -2 * x])
+    assert np.array_equal(tp_gemm.reduce_partials(pm), np.zeros((mp, N)))
+    assert np.array_equal(tp_gemm.reduce_partials(x[None]), x.astype(np.float64))
+    # sums that float32 would get wrong but float64 keeps: 2^24 + 1 - 2^24 = 1
+    big = np.stack([np.full((1, 1), 2.0 ** 24, np.float32), np.ones((1, 1), np.float32),
+                    np.full((1, 1), -2.0 ** 24, np.float32)])
+    assert tp_gemm.reduce_partials(big)[0, 0] == 1.0
+
+
+def test_gemm_rs_P1_is_plain_rounded_gemm():
+    A = wl.small_int_matrix((4, 6), 41, 1)
+    B = wl.small_int_matrix((6, 3), 41, 2)
+    res = tp_gemm.gemm_rs(1, 0, _int_bits(A, "bf16"), _int_bits(B, "bf16"), "bf16",
+                          np.zeros((1, 4, 3), np.float32))
+    assert np.array_equal(res["out"], np.array(_brute_int(A, B), dtype=np.float64))
+
+
+def test_rows_variants_agree_with_definitions():
+    P, M, N, K = 2, 8, 5, 12
+    inp = wl.gemm_rs_inputs(P, M, N, K, "bf16", rank=1, seed=4)
+    A = codec.bf16_decode(inp["A_local"])
+    B = codec.bf16_decode(inp["B_local"])
+    rows = [7, 0, 4, 3]
+    own_rows, out_rows = tp_gemm.gemm_rs_rows(P, 1, inp["A_local"], inp["B_local"], "bf16", inp["partials"], rows)
+    for t, i in enumerate(rows):
+        for j in range(N):
+            ref = sum(A[i, k] * B[k, j] for k in range(K // P))
+            assert abs(own_rows[t, j] - ref) <= 1e-15
+            if i >= 4:
+                red = float(inp["partials"][0][i - 4, j]) + ref
+                assert abs(out_rows[t, j] - red) <= 1e-15
+            else:
+                assert np.isnan(out_rows[t, j])
+
+
+def test_abs_product_bounds_the_sum():
+    inp = wl.gemm_rs_inputs(2, 8, 6, 16, "bf16", rank=0, seed=5)
+    own = tp_gemm.local_product(inp["A_local"], inp["B_local"], "bf16")
+    mag = tp_gemm.abs_product(inp["A_local"], inp["B_local"], "bf16")
+    assert np.all(np.abs(own) <= mag + 1e-18)
+    assert np.all(mag > 0)
+
+
+def test_shape_errors():
+    a = np.zeros((4, 6), np.uint16)
+    with pytest.raises(ValueError):
+        tp_gemm.local_product(a, np.zeros((5, 3), np.uint16), "bf16")
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_rs(3, 0, a, np.zeros((6, 3), np.uint16), "bf16", np.zeros((3, 1, 3), np.float32))
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_rs(2, 0, a, np.zeros((6, 3), np.uint16), "bf16", np.zeros((2, 2, 4), np.float32))
