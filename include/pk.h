@@ -1,0 +1,163 @@
+/*
+ * libpk: one rank's share of the two fused tensor-parallel GEMMs, on one MI355X (gfx950).
+ *
+ *   pk_gemm_rs  GEMM + tile-granular reduce-scatter   (paper sections 3.1.3 and 4.1, figure "GEMM + RS")
+ *   pk_ag_gemm  all-gather + GEMM                     (paper sections 3.1.3 and 4.1, figure "AG + GEMM")
+ *
+ * Notation is the paper's (section 4, experimental setup): P ranks; the GLOBAL GEMM is M x N x K with a
+ * first operand A of M x K and a second operand B of K x N; 16-bit (bf16) inputs, fp32 accumulation.  The
+ * 8-bit input type (OCP e4m3, finite+NaN, with one fp32 scale per tensor) is an extension of this library.
+ * Every matrix is row-major and densely packed (leading dimension = number of columns).
+ *
+ * Peer ranks are not real GPUs here.  What a peer would write into this rank's memory over the fabric (its
+ * partial sums for this rank's output shard; its row-chunk of A) lives in buffers in this GPU's HBM and is
+ * announced through ready flags, exactly as a one-way push into pre-allocated destination buffers would be
+ * (paper section 3.1.4, "pre-allocated destination buffers, direct one-way transfers").  The pk_emu_* calls
+ * play the peers for tests and benchmarks; they are not part of the method.
+ *
+ * Flags (the paper's barrier objects and signal/wait primitives, section 3.2.2 and appendix C): a flag is a
+ * uint32 in device memory.  A datum is ready for a call with epoch e once (int32)(flag - e) >= 0.  Producers
+ * write the data, release at device scope, then store e; consumers poll, acquire, then read the data.  Using a
+ * monotone epoch instead of a counter that must be reset lets back-to-back calls reuse the flag arrays.
+ *
+ * Conventions for every entry point:
+ *   - all pointers are DEVICE pointers unless marked "host";
+ *   - the caller owns every buffer; the library allocates no device memory and keeps no state;
+ *   - calls are asynchronous on `stream` (a hipStream_t, passed as void*); nothing synchronises the device;
+ *   - arguments are validated on the host first; on an error nothing is launched and nothing is written;
+ *   - a wait that exceeds `timeout_us` microseconds makes the kernel write {PK_ERR_TIMEOUT, index, phase, 0}
+ *     to status[0..3] (first error wins) and drain; the host reads it after synchronising the stream.
+ *     timeout_us = 0 selects the default (2 s).  The caller zeroes `status` (4 x uint32) before the call.
+ */
+#ifndef PK_H
+#define PK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PK_OK = 0,
+    PK_ERR_NULL = 1,       /* a required pointer is NULL */
+    PK_ERR_SHAPE = 2,      /* P/M/N/K do not divide as required (see each call) */
+    PK_ERR_DTYPE = 3,      /* unknown dtype, or fp8 without scales */
+    PK_ERR_ALIGN = 4,      /* a matrix pointer is not 16-byte aligned */
+    PK_ERR_RANK = 5,       /* rank outside [0, P) */
+    PK_ERR_ARG = 6,        /* any other invalid argument (phases, order list, ...) */
+    PK_ERR_HIP = 7,        /* a HIP launch failed */
+    PK_ERR_TIMEOUT = 8     /* device side only: reported through `status` */
+} pk_status;
+
+typedef enum { PK_BF16 = 0, PK_FP8_E4M3 = 1 } pk_dtype;
+
+/* phases of pk_gemm_rs (bit mask) */
+#define PK_PHASE_GEMM   1u   /* local GEMM + scatter of finished tiles + per-tile signal */
+#define PK_PHASE_REDUCE 2u   /* wait for the P partials of each own tile, sum, round, store */
+#define PK_PHASE_ALL    3u
+
+/* Flag granularity and derived sizes for a problem; filled by the *_plan calls (host struct). */
+typedef struct {
+    int32_t tile_m, tile_n;       /* rows x cols covered by one ready flag */
+    int32_t tiles_m, tiles_n;     /* flag grid of one shard (GEMM+RS: M/P x N) or of C_local (AG+GEMM) */
+    int64_t flags_per_slot;       /* tiles_m * tiles_n */
+    int64_t local_m, local_n, local_k;   /* the per-rank GEMM */
+} pk_plan;
+
+int pk_version(void);
+const char* pk_status_str(int status);
+
+/*
+ * GEMM + reduce-scatter for rank `rank` (paper section 3.1.3: each finished output tile is sent to the rank
+ * that owns it and accumulated there; section 4.1: second GEMM of the MLP, row-sharded weights).
+ *
+ *   own = A_local . B_local                 (M x N, fp32 accumulate; x scale_a*scale_b for fp8)
+ *   rows R_q = [q*M/P, (q+1)*M/P) of own  -> outgoing[q]       for q != rank   (to rank q)
+ *   rows R_rank of own                    -> partials[rank]
+ *   out_shard = bf16( sum_{p<P} partials[p] )   summed in fp32, slot order 0..P-1, round-to-nearest-even
+ *
+ * Instead of the atomic adds of the paper, every source rank owns a slot of the destination's `partials`
+ * array and the owner adds the P slots once, so the result does not depend on arrival order.
+ *
+ *   A_local   M x K/P      bf16 (2 B) or e4m3 (1 B)
+ *   B_local   K/P x N      same element type
+ *   scale_a, scale_b       one fp32 each, fp8 only (NULL for bf16)
+ *   partials  [P][M/P][N]  fp32.  Slot q != rank is written by peer q (or by pk_emu_deliver_partials);
+ *                          slot `rank` is written by this call.
+ *   outgoing  [P][M/P][N]  fp32.  Slot q != rank receives this rank's tiles for rank q; slot `rank` unused.
+ *                          May be NULL when P == 1.
+ *   flags_in  [P][flags_per_slot] readiness of partials[q][tile]; slot `rank` is signalled by this call.
+ *   flags_out [P][flags_per_slot] signalled by this call when outgoing[q][tile] is complete.
+ *   out_shard M/P x N      bf16
+ *
+ * Requirements: M % P == 0, K % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), N % 8 == 0 (bf16) or
+ * % 16 == 0 (fp8); M/P and N need not be multiples of the tile (edge tiles are partial).  Otherwise
+ * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).
+ */
+pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
+pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_local, const void* B_local,
+                     const float* scale_a, const float* scale_b,
+                     float* partials, float* outgoing,
+                     uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
+                     void* out_shard, uint32_t phases,
+                     uint32_t* status, uint64_t timeout_us, void* stream);
+
+/*
+ * All-gather + GEMM for rank `rank` (paper section 4.1: first GEMM of the MLP, inputs sharded by rows are
+ * gathered, weights column-sharded; section 3.1.3 "inter-SM overlapping": the chunks are moved by dedicated
+ * communicator workers while the compute workers wait on a per-chunk flag before loading).
+ *
+ *   C_local = bf16( A_gathered . B_local )      (M x N/P; x scale_a*scale_b for fp8)
+ *
+ *   A_gathered  M x K   rows R_q = chunk q.  Chunk `rank` is valid at the call; chunk q != rank is valid
+ *                       once chunk_flags[q] has reached `epoch`.
+ *   B_local     K x N/P
+ *   chunk_flags [P]
+ *   C_local     M x N/P bf16
+ *
+ * Output tiles are scheduled chunk by chunk starting from the own chunk, then rank+1, rank+2, ... (mod P).
+ * Requirements: M % P == 0, N % P == 0, K % 64 == 0 (bf16) or % 128 == 0 (fp8), (N/P) % 8 == 0 (bf16) or
+ * % 16 == 0 (fp8).  With P == 1 this is a plain GEMM with bf16 output (chunk_flags may then be NULL).
+ */
+pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
+pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_gathered, const void* B_local,
+                     const float* scale_a, const float* scale_b,
+                     const uint32_t* chunk_flags, uint32_t epoch,
+                     void* C_local,
+                     uint32_t* status, uint64_t timeout_us, void* stream);
+
+/*
+ * Peer emulation (tests and benchmarks only; stands in for what other ranks would push over the fabric).
+ *
+ * pk_emu_deliver_chunks: for i = 0..n_order-1, copy chunk q = order[i] (M/P x K elements of `elem_bytes`
+ * bytes) from staging[q] = staging + q*chunk_bytes into rows R_q of A_gathered, release, set
+ * chunk_flags[q] = epoch, then idle `gap_us` microseconds before the next chunk.
+ *
+ * pk_emu_deliver_partials: for i = 0..n_order-1, q = order[i]: copy every flag tile of staging slot q
+ * ([P][M/P][N] fp32, same layout as `partials`) into partials[q], tile by tile, release and set
+ * flags_in[q][tile] = epoch after each tile; idle `gap_us` between slots.
+ *
+ * `order` is a HOST array of at most PK_EMU_MAX_ORDER distinct ranks (the caller excludes its own rank).
+ * `counters` is device scratch of at least PK_EMU_MAX_ORDER uint32, zeroed by the caller before each call.
+ * Launch these on a second stream BEFORE the consuming call so that their workgroups are resident.
+ */
+#define PK_EMU_MAX_ORDER 64
+pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes,
+                                const void* staging, void* A_gathered,
+                                uint32_t* chunk_flags, uint32_t epoch,
+                                const int* order /* host */, int n_order, uint32_t gap_us,
+                                uint32_t* counters, void* stream);
+pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n,
+                                  const float* staging, float* partials,
+                                  uint32_t* flags_in, uint32_t epoch,
+                                  const int* order /* host */, int n_order, uint32_t gap_us,
+                                  void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PK_H */

@@ -1,0 +1,432 @@
+// libpk: kernels other than the GEMM, and the C-ABI entry points (see include/pk.h).
+#include <hip/hip_runtime.h>
+
+#include "pk_device.h"
+#include "pk_gemm.h"
+
+namespace pk {
+
+// ------------------------------------------------------------------------------------------------
+// Fused reduce of the P partial slots of this rank's shard (paper appendix C `reduce`: load the same
+// tile from every device, reduce, store to local memory; section 3.1.3: the owner accumulates the
+// tiles that the P ranks produced).  Pure streaming: per 8 output elements a thread issues 2 x P
+// independent 16-byte loads, adds in slot order 0..P-1 in fp32, rounds to bf16 and stores 16 bytes.
+// One workgroup handles `rows_sub` rows of one flag tile after waiting for that tile's P flags.
+// ------------------------------------------------------------------------------------------------
+struct ReduceArgs {
+    const float* partials;    // [P][rows][n]
+    uint16_t* out;            // rows x n bf16
+    const uint32_t* flags_in; // [P][flags_per_slot]
+    int32_t P, rows, n;
+    int32_t tile_m, tile_n, tiles_n, sub, rows_sub;
+    int64_t slot_elems, flags_per_slot;
+    uint32_t epoch;
+    uint32_t* status;
+    uint64_t timeout_ticks;
+};
+
+template <int PT>   // PT > 0: compile-time P; PT == 0: runtime P
+__global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
+    const int tid = threadIdx.x;
+    const int tile = blockIdx.x / r.sub;
+    const int sb = blockIdx.x - tile * r.sub;
+    const int tmi = tile / r.tiles_n, tc = tile - tmi * r.tiles_n;
+    const int P = PT > 0 ? PT : r.P;
+
+    // wait (paper appendix C): one lane per source rank polls that rank's flag for this tile
+    int late = 0;
+    if (tid < P) {
+        if (!flag_wait(r.flags_in + (int64_t)tid * r.flags_per_slot + tile, r.epoch, r.timeout_ticks)) {
+            report_timeout(r.status, (uint32_t)tile, 2u);
+            late = 1;
+        }
+    }
+    if (__syncthreads_or(late)) return;
+    acquire_agent();
+
+    const int row_start = tmi * r.tile_m + sb * r.rows_sub;
+    const int row_stop = min(min(row_start + r.rows_sub, (tmi + 1) * r.tile_m), r.rows);
+    const int col0 = tc * r.tile_n;
+    const int cpr = min(r.tile_n, r.n - col0) >> 3;          // 8-element chunks per row of this tile
+    const int total = (row_stop - row_start) * cpr;
+    for (int idx = tid; idx < total; idx += 256) {
+        const int rr = idx / cpr, cc = idx - rr * cpr;
+        const int64_t off = (int64_t)(row_start + rr) * r.n + col0 + cc * 8;
+        const float* src = r.partials + off;
+        f32x4 v0[PT > 0 ? PT : 1], v1[PT > 0 ? PT : 1];
+        f32x4 s0, s1;
+        if constexpr (PT > 0) {
+#pragma unroll
+            for (int p = 0; p < PT; ++p) {
+                v0[p] = __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems));
+                v1[p] = __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems + 4));
+            }
+            s0 = v0[0];
+            s1 = v1[0];
+#pragma unroll
+            for (int p = 1; p < PT; ++p) {
+                s0 += v0[p];
+                s1 += v1[p];
+            }
+        } else {
+            s0 = __builtin_nontemporal_load((const f32x4*)src);
+            s1 = __builtin_nontemporal_load((const f32x4*)(src + 4));
+            for (int p = 1; p < P; ++p) {
+                s0 += __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems));
+                s1 += __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems + 4));
+            }
+        }
+        bf16x8 o = {(__bf16)s0[0], (__bf16)s0[1], (__bf16)s0[2], (__bf16)s0[3],
+                    (__bf16)s1[0], (__bf16)s1[1], (__bf16)s1[2], (__bf16)s1[3]};
+        __builtin_nontemporal_store(o, (bf16x8*)(r.out + off));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Peer emulation (not part of the method): what other ranks' communicator workers would push here.
+// ------------------------------------------------------------------------------------------------
+struct EmuOrder {
+    int32_t n;
+    int32_t q[PK_EMU_MAX_ORDER];
+};
+
+__device__ __forceinline__ void idle_us(uint32_t us) {
+    if (us == 0) return;
+    const uint64_t t0 = wall_clock64();
+    const uint64_t ticks = (uint64_t)us * kWallClockTicksPerUs;
+    while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(16);
+}
+
+__global__ __launch_bounds__(256) void emu_chunks_kernel(const char* staging, char* A_gathered, int64_t chunk_bytes,
+                                                         uint32_t* chunk_flags, uint32_t epoch, EmuOrder ord,
+                                                         uint32_t gap_us, uint32_t* counters) {
+    const int64_t n16 = chunk_bytes >> 4;
+    for (int i = 0; i < ord.n; ++i) {
+        const int q = ord.q[i];
+        const i32x4* src = (const i32x4*)(staging + (int64_t)q * chunk_bytes);
+        i32x4* dst = (i32x4*)(A_gathered + (int64_t)q * chunk_bytes);
+        for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < n16; idx += (int64_t)gridDim.x * 256)
+            dst[idx] = __builtin_nontemporal_load(src + idx);
+        release_agent();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            // the last workgroup to finish its part of the chunk publishes the flag
+            uint32_t old = __hip_atomic_fetch_add(counters + i, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == gridDim.x - 1) flag_signal(chunk_flags + q, epoch);
+        }
+        idle_us(gap_us);
+    }
+}
+
+__global__ __launch_bounds__(256) void emu_partials_kernel(const float* staging, float* partials, uint32_t* flags_in,
+                                                           uint32_t epoch, EmuOrder ord, uint32_t gap_us,
+                                                           int rows, int n, int tile_m, int tile_n,
+                                                           int tiles_m, int tiles_n) {
+    const int64_t slot_elems = (int64_t)rows * n;
+    const int64_t fps = (int64_t)tiles_m * tiles_n;
+    for (int i = 0; i < ord.n; ++i) {
+        const int q = ord.q[i];
+        for (int tile = blockIdx.x; tile < tiles_m * tiles_n; tile += gridDim.x) {
+            const int tmi = tile / tiles_n, tc = tile - tmi * tiles_n;
+            const int r0 = tmi * tile_m, r1 = min(r0 + tile_m, rows);
+            const int c0 = tc * tile_n, w4 = min(tile_n, n - c0) >> 2;
+            const int total = (r1 - r0) * w4;
+            for (int idx = threadIdx.x; idx < total; idx += 256) {
+                const int rr = idx / w4, cc = idx - rr * w4;
+                const int64_t off = (int64_t)q * slot_elems + (int64_t)(r0 + rr) * n + c0 + cc * 4;
+                *(f32x4*)(partials + off) = __builtin_nontemporal_load((const f32x4*)(staging + off));
+            }
+            release_agent();
+            __syncthreads();
+            if (threadIdx.x == 0) flag_signal(flags_in + (int64_t)q * fps + tile, epoch);
+        }
+        idle_us(gap_us);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------------
+struct TileCfg {
+    int bm, bn;
+};
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// 256 x 256 tiles when they still give every CU a tile, else 128 x 128.
+static TileCfg pick_tile(int P, int64_t rows_per_shard, int64_t n) {
+    const int64_t big = (int64_t)P * ceil_div(rows_per_shard, 256) * ceil_div(n, 256);
+    if (rows_per_shard >= 256 && n >= 256 && big >= 256) return {256, 256};
+    return {128, 128};
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, bool rs,
+                            int64_t* lm, int64_t* ln, int64_t* lk) {
+    if (dt != PK_BF16 && dt != PK_FP8_E4M3) return PK_ERR_DTYPE;
+    if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || N < 1 || K < 1) return PK_ERR_SHAPE;
+    if (M % P) return PK_ERR_SHAPE;
+    if (rs ? (K % P) : (N % P)) return PK_ERR_SHAPE;
+    const int64_t m = M, n = rs ? N : N / P, k = rs ? K / P : K;
+    const int kt = dt == PK_FP8_E4M3 ? 128 : 64, nv = dt == PK_FP8_E4M3 ? 16 : 8;
+    if (k % kt || n % nv) return PK_ERR_SHAPE;
+    if (m > (1 << 30) || n > (1 << 30) || k > (1 << 30)) return PK_ERR_SHAPE;
+    *lm = m;
+    *ln = n;
+    *lk = k;
+    return PK_OK;
+}
+
+static pk_status make_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, bool rs, pk_plan* plan) {
+    if (!plan) return PK_ERR_NULL;
+    int64_t m, n, k;
+    pk_status st = check_dims(P, M, N, K, dt, rs, &m, &n, &k);
+    if (st != PK_OK) return st;
+    const TileCfg tc = pick_tile(P, M / P, n);
+    plan->tile_m = tc.bm;
+    plan->tile_n = tc.bn;
+    plan->tiles_m = (int32_t)ceil_div(M / P, tc.bm);
+    plan->tiles_n = (int32_t)ceil_div(n, tc.bn);
+    plan->flags_per_slot = (int64_t)plan->tiles_m * plan->tiles_n;
+    plan->local_m = m;
+    plan->local_n = n;
+    plan->local_k = k;
+    return PK_OK;
+}
+
+template <int BM, int BN, bool FP8, int EPI>
+static pk_status launch_gemm(const GemmArgs& a, int grid, hipStream_t stream) {
+    static bool configured = false;
+    auto kern = gemm_kernel<BM, BN, FP8, EPI>;
+    constexpr int lds = gemm_lds_bytes<BM, BN>();
+    if (!configured) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+            return PK_ERR_HIP;
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, a);
+    return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
+}
+
+template <int EPI>
+static pk_status dispatch_gemm(const GemmArgs& a, int grid, const TileCfg& tc, bool fp8, hipStream_t stream) {
+    if (tc.bm == 256) {
+        return fp8 ? launch_gemm<256, 256, true, EPI>(a, grid, stream) : launch_gemm<256, 256, false, EPI>(a, grid, stream);
+    }
+    return fp8 ? launch_gemm<128, 128, true, EPI>(a, grid, stream) : launch_gemm<128, 128, false, EPI>(a, grid, stream);
+}
+
+static uint64_t timeout_ticks(uint64_t timeout_us) {
+    if (timeout_us == 0) timeout_us = 2000000;
+    return timeout_us * kWallClockTicksPerUs;
+}
+
+}  // namespace pk
+
+using namespace pk;
+
+extern "C" {
+
+int pk_version(void) { return 1; }
+
+const char* pk_status_str(int s) {
+    switch (s) {
+        case PK_OK: return "ok";
+        case PK_ERR_NULL: return "null pointer";
+        case PK_ERR_SHAPE: return "unsupported shape";
+        case PK_ERR_DTYPE: return "bad dtype or missing scales";
+        case PK_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case PK_ERR_RANK: return "rank out of range";
+        case PK_ERR_ARG: return "invalid argument";
+        case PK_ERR_HIP: return "HIP launch failed";
+        case PK_ERR_TIMEOUT: return "timed out waiting for a ready flag";
+        default: return "unknown status";
+    }
+}
+
+pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    return make_plan(P, M, N, K, dt, true, plan);
+}
+
+pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    return make_plan(P, M, N, K, dt, false, plan);
+}
+
+pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
+                     float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
+                     void* out_shard, uint32_t phases, uint32_t* status, uint64_t timeout_us, void* stream) {
+    pk_plan pl;
+    pk_status st = make_plan(P, M, N, K, dt, true, &pl);
+    if (st != PK_OK) return st;
+    if (rank < 0 || rank >= P) return PK_ERR_RANK;
+    if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
+    const bool fp8 = dt == PK_FP8_E4M3;
+    const bool do_gemm = phases & PK_PHASE_GEMM, do_reduce = phases & PK_PHASE_REDUCE;
+    if (!partials || !flags_in || !status) return PK_ERR_NULL;
+    if (do_gemm && (!A_local || !B_local)) return PK_ERR_NULL;
+    if (do_gemm && P > 1 && (!outgoing || !flags_out)) return PK_ERR_NULL;
+    if (do_reduce && !out_shard) return PK_ERR_NULL;
+    if (do_gemm && fp8 && (!scale_a || !scale_b)) return PK_ERR_DTYPE;
+    if (!aligned16(A_local) || !aligned16(B_local) || !aligned16(partials) || !aligned16(outgoing) ||
+        !aligned16(out_shard))
+        return PK_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const TileCfg tc = {pl.tile_m, pl.tile_n};
+    const int64_t rows = M / P;
+
+    if (do_gemm) {
+        GemmArgs a = {};
+        const int elem = fp8 ? 1 : 2;
+        a.A = (const char*)A_local;
+        a.B = (const char*)B_local;
+        a.lda = pl.local_k * elem;
+        a.ldb = pl.local_n * elem;
+        a.n = (int32_t)pl.local_n;
+        a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
+        a.rows_per_shard = (int32_t)rows;
+        a.tiles_m_shard = pl.tiles_m;
+        a.tiles_n = pl.tiles_n;
+        a.grp_tile_rows = P * pl.tiles_m;
+        a.n_groups = 1;
+        a.group0 = 0;
+        const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
+        a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
+        a.rank = rank;
+        a.partials = partials;
+        a.outgoing = outgoing;
+        a.flags_in = flags_in;
+        a.flags_out = flags_out;
+        a.slot_elems = rows * pl.local_n;
+        a.flags_per_slot = pl.flags_per_slot;
+        a.scale_a = scale_a;
+        a.scale_b = scale_b;
+        a.epoch = epoch;
+        a.status = status;
+        a.timeout_ticks = timeout_ticks(timeout_us);
+        st = dispatch_gemm<EPI_RS>(a, a.wg_per_group, tc, fp8, s);
+        if (st != PK_OK) return st;
+    }
+    if (do_reduce) {
+        ReduceArgs r = {};
+        r.partials = partials;
+        r.out = (uint16_t*)out_shard;
+        r.flags_in = flags_in;
+        r.P = P;
+        r.rows = (int32_t)rows;
+        r.n = (int32_t)pl.local_n;
+        r.tile_m = pl.tile_m;
+        r.tile_n = pl.tile_n;
+        r.tiles_n = pl.tiles_n;
+        r.sub = pl.tile_m / 32;
+        r.rows_sub = 32;
+        r.slot_elems = rows * pl.local_n;
+        r.flags_per_slot = pl.flags_per_slot;
+        r.epoch = epoch;
+        r.status = status;
+        r.timeout_ticks = timeout_ticks(timeout_us);
+        const int grid = (int)(pl.flags_per_slot * r.sub);
+        switch (P) {
+            case 1: hipLaunchKernelGGL(reduce_kernel<1>, dim3(grid), dim3(256), 0, s, r); break;
+            case 2: hipLaunchKernelGGL(reduce_kernel<2>, dim3(grid), dim3(256), 0, s, r); break;
+            case 4: hipLaunchKernelGGL(reduce_kernel<4>, dim3(grid), dim3(256), 0, s, r); break;
+            case 8: hipLaunchKernelGGL(reduce_kernel<8>, dim3(grid), dim3(256), 0, s, r); break;
+            default: hipLaunchKernelGGL(reduce_kernel<0>, dim3(grid), dim3(256), 0, s, r); break;
+        }
+        if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
+    }
+    return PK_OK;
+}
+
+pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
+                     const uint32_t* chunk_flags, uint32_t epoch, void* C_local,
+                     uint32_t* status, uint64_t timeout_us, void* stream) {
+    pk_plan pl;
+    pk_status st = make_plan(P, M, N, K, dt, false, &pl);
+    if (st != PK_OK) return st;
+    if (rank < 0 || rank >= P) return PK_ERR_RANK;
+    const bool fp8 = dt == PK_FP8_E4M3;
+    if (!A_gathered || !B_local || !C_local || !status) return PK_ERR_NULL;
+    if (P > 1 && !chunk_flags) return PK_ERR_NULL;
+    if (fp8 && (!scale_a || !scale_b)) return PK_ERR_DTYPE;
+    if (!aligned16(A_gathered) || !aligned16(B_local) || !aligned16(C_local)) return PK_ERR_ALIGN;
+    const TileCfg tc = {pl.tile_m, pl.tile_n};
+    const int elem = fp8 ? 1 : 2;
+    GemmArgs a = {};
+    a.A = (const char*)A_gathered;
+    a.B = (const char*)B_local;
+    a.lda = pl.local_k * elem;
+    a.ldb = pl.local_n * elem;
+    a.n = (int32_t)pl.local_n;
+    a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
+    a.rows_per_shard = (int32_t)(M / P);
+    a.tiles_m_shard = pl.tiles_m;
+    a.tiles_n = pl.tiles_n;
+    a.grp_tile_rows = pl.tiles_m;
+    a.n_groups = P;
+    a.group0 = rank;
+    const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
+    a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
+    a.rank = rank;
+    a.C = (uint16_t*)C_local;
+    a.chunk_flags = chunk_flags;
+    a.scale_a = scale_a;
+    a.scale_b = scale_b;
+    a.epoch = epoch;
+    a.status = status;
+    a.timeout_ticks = timeout_ticks(timeout_us);
+    return dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, tc, fp8, (hipStream_t)stream);
+}
+
+static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
+    if (n_order < 0 || n_order > PK_EMU_MAX_ORDER) return PK_ERR_ARG;
+    if (n_order > 0 && !order) return PK_ERR_NULL;
+    o->n = n_order;
+    for (int i = 0; i < n_order; ++i) {
+        if (order[i] < 0 || order[i] >= P) return PK_ERR_ARG;
+        for (int j = 0; j < i; ++j)
+            if (order[j] == order[i]) return PK_ERR_ARG;
+        o->q[i] = order[i];
+    }
+    return PK_OK;
+}
+
+pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes, const void* staging, void* A_gathered,
+                                uint32_t* chunk_flags, uint32_t epoch, const int* order, int n_order,
+                                uint32_t gap_us, uint32_t* counters, void* stream) {
+    if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || K < 1 || M % P) return PK_ERR_SHAPE;
+    if (elem_bytes != 1 && elem_bytes != 2) return PK_ERR_DTYPE;
+    if (!staging || !A_gathered || !chunk_flags || !counters) return PK_ERR_NULL;
+    const int64_t chunk_bytes = (M / P) * K * elem_bytes;
+    if (chunk_bytes % 16) return PK_ERR_SHAPE;
+    if (!aligned16(staging) || !aligned16(A_gathered)) return PK_ERR_ALIGN;
+    EmuOrder o;
+    pk_status st = make_order(order, n_order, P, &o);
+    if (st != PK_OK) return st;
+    if (n_order == 0) return PK_OK;
+    hipLaunchKernelGGL(emu_chunks_kernel, dim3(32), dim3(256), 0, (hipStream_t)stream, (const char*)staging,
+                       (char*)A_gathered, chunk_bytes, chunk_flags, epoch, o, gap_us, counters);
+    return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
+}
+
+pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n, const float* staging,
+                                  float* partials, uint32_t* flags_in, uint32_t epoch, const int* order, int n_order,
+                                  uint32_t gap_us, void* stream) {
+    if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || N < 1 || M % P || N % 4) return PK_ERR_SHAPE;
+    if (tile_m < 1 || tile_n < 4 || tile_n % 4) return PK_ERR_ARG;
+    if (!staging || !partials || !flags_in) return PK_ERR_NULL;
+    if (!aligned16(staging) || !aligned16(partials)) return PK_ERR_ALIGN;
+    EmuOrder o;
+    pk_status st = make_order(order, n_order, P, &o);
+    if (st != PK_OK) return st;
+    if (n_order == 0) return PK_OK;
+    const int rows = (int)(M / P);
+    const int tiles_m = (int)ceil_div(rows, tile_m), tiles_n = (int)ceil_div(N, tile_n);
+    hipLaunchKernelGGL(emu_partials_kernel, dim3(32), dim3(256), 0, (hipStream_t)stream, staging, partials, flags_in,
+                       epoch, o, gap_us, rows, (int)N, tile_m, tile_n, tiles_m, tiles_n);
+    return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
+}
+
+}  // extern "C"

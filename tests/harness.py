@@ -1,0 +1,123 @@
+"""Glue for the GPU parity tests: uploads seeded numpy inputs, calls libpk through its binding,
+downloads the results.  No arithmetic of the method happens here."""
+import numpy as np
+import torch
+
+from paper_2511_13940_amd import pk
+
+NAN_POISON = float("nan")
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def elem_view(bits, dtype):
+    """numpy uint16/uint8 bit patterns -> device tensor of raw bits."""
+    if dtype == "bf16":
+        return dev(bits.view(np.int16))
+    return dev(bits)
+
+
+def scale_t(s):
+    return None if s is None else torch.tensor([float(s)], dtype=torch.float32, device="cuda")
+
+
+def bits_of(t):
+    """device bf16-bit tensor (int16) -> numpy uint16."""
+    return t.cpu().numpy().view(np.uint16)
+
+
+def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
+                epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
+                withhold=None, state=None):
+    """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
+
+    deliver = "pre": peer slots and their flags are in place before the call.
+    deliver = "emu": peer slots start as NaN; pk_emu_deliver_partials copies them in on a second stream,
+                     in `order`, with `gap_us` between slots, launched before the op.
+    withhold: a (q, tile) whose flag is never set (timeout tests; "pre" only).
+    Returns dict with out_bits (uint16), outgoing, partials_after, flags_out, flags_in, status, plan.
+    """
+    plan = pk.pk_gemm_rs_plan(P, M, N, K, dtype)
+    mp = M // P
+    fps = plan.flags_per_slot
+    A = elem_view(A_bits, dtype)
+    B = elem_view(B_bits, dtype)
+    sa, sb = scale_t(scale_a), scale_t(scale_b)
+    out = torch.full((mp, N), -1, dtype=torch.int16, device="cuda")
+    outgoing = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+    flags_in = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
+    flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    peers = [q for q in range(P) if q != rank]
+    if order is None:
+        order = peers
+    main = torch.cuda.current_stream()
+    if deliver == "pre":
+        part = dev(partials.astype(np.float32))
+        part[rank].fill_(NAN_POISON)
+        for q in peers:
+            flags_in[q].fill_(epoch)
+        if withhold is not None:
+            flags_in[withhold[0], withhold[1]] = epoch - 1
+        torch.cuda.synchronize()
+    else:
+        staging = dev(partials.astype(np.float32))
+        part = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        pk.pk_emu_deliver_partials(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch,
+                                   list(order), gap_us, stream=side)
+    pk.pk_gemm_rs(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
+                  flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main)
+    torch.cuda.synchronize()
+    return {"out_bits": bits_of(out), "outgoing": outgoing.cpu().numpy(), "partials_after": part.cpu().numpy(),
+            "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
+            "status": status.cpu().numpy(), "plan": plan}
+
+
+def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None,
+                epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None):
+    """One pk_ag_gemm call.  chunks: list of P numpy bit arrays (M/P x K).
+
+    deliver = "pre": every chunk is in A_gathered with its flag set before the call.
+    deliver = "emu": only the own chunk is in place; the others are filled with a poison pattern and
+                     pk_emu_deliver_chunks copies them in on a second stream in `order`.
+    withhold: a chunk index whose flag is never set ("pre" only).
+    """
+    mp = M // P
+    elem = 2 if dtype == "bf16" else 1
+    npdt = np.uint16 if dtype == "bf16" else np.uint8
+    poison = 0x7FC1 if dtype == "bf16" else 0x7F          # NaN patterns of the two formats
+    B = elem_view(B_bits, dtype)
+    sa, sb = scale_t(scale_a), scale_t(scale_b)
+    C = torch.full((M, N // P), -1, dtype=torch.int16, device="cuda")
+    flags = torch.zeros(P, dtype=torch.int32, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    peers = [q for q in range(P) if q != rank]
+    if order is None:
+        order = [(rank + d) % P for d in range(1, P)]
+    main = torch.cuda.current_stream()
+    full = np.concatenate([np.asarray(c, dtype=npdt) for c in chunks], axis=0)
+    if deliver == "pre":
+        A = elem_view(full, dtype)
+        for q in peers:
+            flags[q] = epoch
+        if withhold is not None:
+            flags[withhold] = epoch - 1
+        torch.cuda.synchronize()
+    else:
+        staging = elem_view(full, dtype)
+        start = np.full_like(full, poison)
+        start[rank * mp:(rank + 1) * mp] = full[rank * mp:(rank + 1) * mp]
+        A = elem_view(start, dtype)
+        counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        pk.pk_emu_deliver_chunks(P, M, K, elem, staging, A, flags, epoch, list(order), gap_us, counters, stream=side)
+    pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,
+                  timeout_us, stream=main)
+    torch.cuda.synchronize()
+    return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy(),
+            "flags": flags.cpu().numpy()}

@@ -1,0 +1,121 @@
+"""The C-ABI boundary without a GPU: the library loads, exports what include/pk.h declares, and its host-side
+validation returns the documented codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_13940_amd import pk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "pk.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(pk_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = pk.lib()
+    names = _declared()
+    assert set(names) == set(pk.EXPORTS), names
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings():
+    assert pk.pk_version() >= 1
+    seen = {pk.status_str(c) for c in range(9)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert pk.status_str(99) == "unknown status"
+
+
+def test_plans():
+    p = pk.pk_gemm_rs_plan(8, 8192, 8192, 28672, "bf16")
+    assert (p.tile_m, p.tile_n, p.tiles_m, p.tiles_n, p.flags_per_slot) == (256, 256, 4, 32, 128)
+    assert (p.local_m, p.local_n, p.local_k) == (8192, 8192, 3584)
+    p = pk.pk_ag_gemm_plan(8, 8192, 28672, 8192, "bf16")
+    assert (p.tile_m, p.tiles_m, p.tiles_n, p.local_n, p.local_k) == (256, 4, 14, 3584, 8192)
+    p = pk.pk_gemm_rs_plan(2, 256, 256, 512, "bf16")
+    assert (p.tile_m, p.tile_n, p.tiles_m, p.tiles_n) == (128, 128, 1, 2)
+    p = pk.pk_gemm_rs_plan(2, 2 * 200, 264, 256, "bf16")            # ragged: edge tiles are partial
+    assert (p.tiles_m, p.tiles_n) == (2, 3)
+    p = pk.pk_gemm_rs_plan(8, 16384, 16384, 16384, "fp8")
+    assert (p.tile_m, p.flags_per_slot, p.local_k) == (256, 8 * 64, 2048)
+
+
+@pytest.mark.parametrize("args,code", [
+    ((0, 256, 256, 512, pk.BF16), pk.ERR_SHAPE),          # P < 1
+    ((3, 256, 256, 512, pk.BF16), pk.ERR_SHAPE),          # M % P
+    ((2, 256, 256, 510, pk.BF16), pk.ERR_SHAPE),          # K/P not a multiple of 64
+    ((2, 256, 252, 512, pk.BF16), pk.ERR_SHAPE),          # N % 8
+    ((2, 256, 256, 384, pk.FP8_E4M3), pk.ERR_SHAPE),      # fp8: K/P % 128
+    ((2, 256, 256, 512, 7), pk.ERR_DTYPE),
+    ((2, 0, 256, 512, pk.BF16), pk.ERR_SHAPE),            # empty problem
+])
+def test_plan_errors(args, code):
+    plan = pk.Plan()
+    assert pk.lib().pk_gemm_rs_plan(*args, ctypes.byref(plan)) == code
+    assert pk.lib().pk_gemm_rs_plan(2, 256, 256, 512, pk.BF16, None) == pk.ERR_NULL
+
+
+def _rs(P=2, rank=0, M=256, N=256, K=512, dt=pk.BF16, A=0x1000, B=0x2000, sa=None, sb=None, part=0x3000,
+        outg=0x4000, fin=0x5000, fout=0x6000, out=0x7000, phases=3, status=0x8000):
+    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, status, 0, None)
+
+
+def test_gemm_rs_argument_errors_launch_nothing():
+    """Fake non-null pointers: every call below must be rejected on the host (a launch would need a GPU)."""
+    assert _rs(rank=2) == pk.ERR_RANK
+    assert _rs(rank=-1) == pk.ERR_RANK
+    assert _rs(A=None) == pk.ERR_NULL
+    assert _rs(part=None) == pk.ERR_NULL
+    assert _rs(outg=None) == pk.ERR_NULL
+    assert _rs(status=None) == pk.ERR_NULL
+    assert _rs(out=None) == pk.ERR_NULL
+    assert _rs(A=0x1008) == pk.ERR_ALIGN
+    assert _rs(out=0x7004) == pk.ERR_ALIGN
+    assert _rs(phases=0) == pk.ERR_ARG
+    assert _rs(phases=4) == pk.ERR_ARG
+    assert _rs(dt=pk.FP8_E4M3, K=256) == pk.ERR_DTYPE       # fp8 without scales
+    assert _rs(M=255) == pk.ERR_SHAPE
+    assert _rs(dt=5) == pk.ERR_DTYPE
+
+
+def test_ag_gemm_argument_errors_launch_nothing():
+    f = pk.lib().pk_ag_gemm
+
+    def ag(P=4, rank=0, M=2048, N=4096, K=2048, dt=pk.BF16, A=0x1000, B=0x2000, flags=0x3000, C=0x4000, status=0x5000):
+        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, status, 0, None)
+
+    assert ag(rank=4) == pk.ERR_RANK
+    assert ag(N=4098) == pk.ERR_SHAPE        # N % P
+    assert ag(N=4 * 1028) == pk.ERR_SHAPE    # (N/P) % 8
+    assert ag(K=2000) == pk.ERR_SHAPE
+    assert ag(A=None) == pk.ERR_NULL
+    assert ag(flags=None) == pk.ERR_NULL
+    assert ag(C=0x4002) == pk.ERR_ALIGN
+    assert ag(dt=pk.FP8_E4M3) == pk.ERR_DTYPE
+
+
+def test_emulator_argument_errors_launch_nothing():
+    L = pk.lib()
+    order = (ctypes.c_int * 3)(1, 2, 2)
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_ARG
+    order = (ctypes.c_int * 3)(1, 2, 4)
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_ARG
+    order = (ctypes.c_int * 3)(1, 2, 3)
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 4, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_DTYPE
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, None, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_NULL
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0x4000, None) == pk.OK
+    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 65, 0, None) == pk.ERR_ARG
+    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 130, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, None) == pk.ERR_ARG
+    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, None) == pk.OK
+
+
+def test_binding_raises_pk_error():
+    with pytest.raises(pk.PkError) as e:
+        pk.pk_gemm_rs_plan(3, 256, 256, 512, "bf16")
+    assert e.value.code == pk.ERR_SHAPE
