@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-rank tensor-parallel hot path on one MI355X.
+
+One step = one pass over the MLP share of a 70B-class model under 8-way tensor parallelism:
+  pk_ag_gemm  (cfg4: A gathered from 8 chunks of 1024 x 8192, B_local 8192 x 3584)   -> tile schedule,
+              per-chunk flag wait, MFMA main loop, bf16 epilogue
+  pk_gemm_rs  (cfg3: A_local 8192 x 3584, B_local 3584 x 8192, 7 peer partials)      -> tile schedule, MFMA
+              main loop, fp32 scatter epilogue + per-tile signal, fused reduce of the 8 partial slots
+with every input (operands, the peers' chunks and partial sums, their ready flags) resident in HBM when the
+timed region starts.  The metric is the paper's "observed average compute throughput": flops of the two
+local GEMMs divided by the time of the step.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}      # MI355X dense MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing / parity leg")
+    ap.add_argument("--extras", action="store_true", help="also time the phases alone and the live-arrival variants")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs one rank's share on ONE GPU (peers are emulated in the same HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_13940_amd import pk, workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    pk.lib()                                            # fail loudly if the HIP library is missing
+    rank = 0
+    c3, c4 = wl.CONFIGS["cfg3"], wl.CONFIGS["cfg4"]
+
+    # ---------------- inputs (seeded, synthetic), uploaded once ----------------
+    t0 = time.time()
+    i3 = wl.gemm_rs_inputs(c3.P, c3.M, c3.N, c3.K, c3.dtype, rank, seed=0, order=c3.order)
+    i4 = wl.ag_gemm_inputs(c4.P, c4.M, c4.N, c4.K, c4.dtype, rank, seed=0, order=c4.order)
+    a4_full = np.concatenate(i4["chunks"], axis=0)
+    gen_s = time.time() - t0
+
+    def dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+    p3 = pk.pk_gemm_rs_plan(c3.P, c3.M, c3.N, c3.K, c3.dtype)
+    mp3 = c3.M // c3.P
+    A3, B3 = dev(i3["A_local"].view(np.int16)), dev(i3["B_local"].view(np.int16))
+    part = dev(i3["partials"])
+    outgoing = torch.zeros((c3.P, mp3, c3.N), dtype=torch.float32, device="cuda")
+    out3 = torch.zeros((mp3, c3.N), dtype=torch.int16, device="cuda")
+    flags_in = torch.zeros((c3.P, p3.flags_per_slot), dtype=torch.int32, device="cuda")
+    flags_out = torch.zeros_like(flags_in)
+    for q in range(c3.P):
+        if q != rank:
+            flags_in[q].fill_(0x7FFFFFFF)               # peers' partials are resident: ready for every epoch
+    A4, B4 = dev(a4_full.view(np.int16)), dev(i4["B_local"].view(np.int16))
+    C4 = torch.zeros((c4.M, c4.N // c4.P), dtype=torch.int16, device="cuda")
+    chunk_flags = torch.full((c4.P,), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(epoch, ev=None):
+        if ev:
+            ev[0].record(stream)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, A4, B4, None, None, chunk_flags, epoch, C4, status)
+        if ev:
+            ev[1].record(stream)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, A3, B3, None, None, part, outgoing,
+                      flags_in, flags_out, epoch, out3, pk.PHASE_GEMM, status)
+        if ev:
+            ev[2].record(stream)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, None, None, None, None, part, None,
+                      flags_in, None, epoch, out3, pk.PHASE_REDUCE, status)
+        if ev:
+            ev[3].record(stream)
+
+    epoch = 0
+    for _ in range(args.warmup):
+        epoch += 1
+        step(epoch)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        epoch += 1
+        step(epoch, evs[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert status[0].item() == 0, f"device status {status.tolist()}"
+
+    ms_step = wall * 1e3 / args.steps
+    k_ag = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    k_rs = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    k_red = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    flops = c3.flops + c4.flops
+    value = flops / (ms_step * 1e-3) / 1e12
+
+    # ---------------- roofline of the dominant kernel ----------------
+    red_bytes = c3.M * c3.N * 4 + mp3 * c3.N * 2           # P slots of fp32 read + bf16 shard written
+    kernels = {
+        "gemm_kernel<256,256,bf16,AG> (cfg4)": {"ms": k_ag, "TFLOP/s": c4.flops / (k_ag * 1e-3) / 1e12},
+        "gemm_kernel<256,256,bf16,RS> (cfg3)": {"ms": k_rs, "TFLOP/s": c3.flops / (k_rs * 1e-3) / 1e12},
+        "reduce_kernel<8> (cfg3)": {"ms": k_red, "GB/s": red_bytes / (k_red * 1e-3) / 1e9},
+    }
+    dom = "gemm_kernel<256,256,bf16,RS> (cfg3)" if k_rs >= k_ag else "gemm_kernel<256,256,bf16,AG> (cfg4)"
+    ach = kernels[dom]["TFLOP/s"]
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK_TFLOPS["bf16"],
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS["bf16"], 4), "traffic": None,
+                "kernel_ms": round(kernels[dom]["ms"], 4)}
+    reduce_roofline = {"bound": "hbm", "kernel": "reduce_kernel<8> (cfg3)",
+                       "achieved": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"], 1), "peak": PEAK_HBM_GBS,
+                       "unit": "GB/s", "frac": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"] / PEAK_HBM_GBS, 4),
+                       "kernel_ms": round(k_red, 4)}
+
+    result = {
+        "metric": "per-rank TFLOP/s (GEMM+RS, AG+GEMM) and % of MFMA/HBM roofline, 1 MI355X",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg4 AG+GEMM (P=8, A 8x[1024x8192], B_local 8192x3584) + cfg3 GEMM+RS "
+                               "(P=8, A_local 8192x3584, B_local 3584x8192, 7 fp32 peer partials 1024x8192); "
+                               "70B-MLP TP=8 share, rank 0, peers' data pre-landed with flags set",
+                   "flops_per_step": flops},
+        "roofline": roofline,
+        "reduce_roofline": reduce_roofline,
+        "kernels": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in kernels.items()},
+        "frac_of_mfma_peak_whole_step": round(value / PEAK_TFLOPS["bf16"], 4),
+    }
+
+    if args.extras:
+        result["extras"] = extras(pk, wl, torch, np, locals())
+
+    # ---------------- CPU baseline: the oracle as it stands, and parity of this run's outputs ----------------
+    if not args.no_cpu_baseline:
+        from oracle import codec, tp_gemm
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        rows3 = np.arange(0, c3.M)                      # the whole workload: the oracle takes seconds here
+        rows4 = np.arange(0, c4.M)
+        t0 = time.perf_counter()
+        own_rows, out_rows = tp_gemm.gemm_rs_rows(c3.P, rank, i3["A_local"], i3["B_local"], c3.dtype,
+                                                  i3["partials"], rows3)
+        c_rows = tp_gemm.ag_gemm(c4.P, rank, a4_full, i4["B_local"], c4.dtype, rows=rows4)["C"]
+        cpu_s = time.perf_counter() - t0
+        sample_flops = 2 * len(rows3) * c3.N * (c3.K // c3.P) + 2 * len(rows4) * (c4.N // c4.P) * c4.K
+        result["cpu_baseline"] = {"value": round(sample_flops / cpu_s / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores),
+                                  "kind": "oracle", "seconds": round(cpu_s, 2),
+                                  "sample": "the whole step: both local GEMMs in full (8192 rows each, all columns, full K) "
+                                            "plus the 8-slot reduce of the own shard"}
+        # parity of the benchmarked buffers on the sampled rows
+        gate = lambda g, r: float(np.max(np.abs(g - r) / (np.abs(r) + 1.0)))
+        own_rank_rows = rows3[rows3 // mp3 == rank]
+        got3 = codec.bf16_decode(out3.cpu().numpy().view(np.uint16))[own_rank_rows - rank * mp3]
+        ref3 = out_rows[rows3 // mp3 == rank]
+        got4 = codec.bf16_decode(C4.cpu().numpy().view(np.uint16))[rows4]
+        og = outgoing.cpu().numpy()
+        scat_err = 0.0
+        for q in range(c3.P):
+            if q == rank:
+                continue
+            sel = rows3 // mp3 == q
+            scat_err = max(scat_err, gate(og[q][rows3[sel] - q * mp3], own_rows[sel]))
+        result["parity"] = {"metric": "max|gpu-ref|/(|ref|+1) on the sampled rows", "gemm_rs_out": gate(got3, ref3),
+                            "gemm_rs_outgoing": scat_err, "ag_gemm_C": gate(got4, c_rows), "tolerance": 1e-2}
+        assert max(result["parity"]["gemm_rs_out"], scat_err, result["parity"]["ag_gemm_C"]) <= 1e-2, result["parity"]
+
+    result["setup_seconds"] = round(gen_s, 1)
+    print(json.dumps(result))
+
+
+def extras(pk, wl, torch, np, L):
+    """Informational timings: bare GEMM, reduce and gather phases alone, live arrival."""
+    c3, c4, rank = L["c3"], L["c4"], L["rank"]
+    stream = L["stream"]
+    out = {}
+
+    def timeit(fn, n=10, w=3):
+        for _ in range(w):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(n):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    # bare GEMM of the cfg3 local shape with bf16 output (P = 1 all-gather GEMM): the "GEMM" column of the paper's Table 3
+    m, n, k = c3.local_mnk
+    Cg = torch.zeros((m, n), dtype=torch.int16, device="cuda")
+    t_gemm = timeit(lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", L["A3"], L["B3"], None, None, None, 1, Cg, L["status"]))
+    ep = [10 ** 6]
+
+    def fused():
+        ep[0] += 1
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                      L["flags_in"], L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, L["status"])
+    t_fused = timeit(fused)
+    out["table3_style"] = {"gemm_ms": round(t_gemm, 4), "gemm_rs_ms": round(t_fused, 4),
+                           "comm_ratio": round((t_fused - t_gemm) / t_fused, 4)}
+
+    # gather phase alone: the emulated communicator moving the 7 peer chunks (read + write)
+    staging = L["A4"].clone()
+    counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
+    order = L["i4"]["order"]
+
+    def gather():
+        counters.zero_()
+        pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], L["chunk_flags"], 0x7FFFFFFF, order, 0, counters)
+    t_g = timeit(gather)
+    moved = 2 * (c4.P - 1) * (c4.M // c4.P) * c4.K * 2
+    out["gather_phase"] = {"ms": round(t_g, 4), "GB/s": round(moved / (t_g * 1e-3) / 1e9, 1),
+                           "frac_of_hbm_peak": round(moved / (t_g * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    return out
+
+
+if __name__ == "__main__":
+    main()
