@@ -1,16 +1,21 @@
 // The MFMA GEMM kernel behind pk_gemm_rs and pk_ag_gemm (gfx950 only).
 //
-// One workgroup of 4 waves (2 x 2) computes one BM x BN tile of the local product; each wave owns a
+// A persistent workgroup of 4 waves (2 x 2) walks over BM x BN tiles of the local product; each wave owns a
 // (BM/2) x (BN/2) sub-tile as (BM/64) x (BN/64) accumulators of the 32x32 MFMA.  Per k-tile of 128 bytes
 // of A-row (64 bf16 or 128 fp8):
 //   * the A tile (BM x 128 B) and B tile (128*BN B) are copied global -> LDS with 16-byte direct-to-LDS
-//     loads (no VGPR staging) into the buffer not being computed on (two stages);
+//     loads (no VGPR staging) one k-tile ahead, into the LDS stage that is not being read (two stages);
 //   * A fragments are read with ds_read_b128, B fragments with the transposing ds_read_b64_tr_b16 /
 //     _tr_b8 (B is row-major K x N, the MFMA wants k-contiguous lanes);
 //   * both LDS tiles are XOR-swizzled at 16-byte-chunk granularity; a direct-to-LDS load writes lane l's
-//     16 bytes at base + 16*l, so the swizzle is applied by choosing which global chunk each lane fetches.
+//     16 bytes at base + 16*l, so the swizzle is applied by choosing which global chunk each lane fetches;
+//   * the loop is software-pipelined: the fragments of k-step s+1 are read while the MFMAs of step s issue,
+//     and the single barrier of a k-tile sits before its last k-step, so the next tile's loads and the
+//     first fragments of the next k-tile are issued under that step's MFMAs.
 // The operands are passed to the MFMA swapped (B fragment first), which leaves each lane with four
-// consecutive columns of one row, i.e. a 16-byte fp32 (8-byte bf16) store per accumulator quad.
+// consecutive columns of one row; the epilogue transposes through a 32 KB LDS staging area so that global
+// stores are 16 bytes per lane over whole row segments of the wave's sub-tile.  The epilogue of tile t runs
+// after the first loads of tile t+1 have been issued.
 //
 // Roles of the paper's program template (section 3.2.3, appendix D): the direct-to-LDS loads are the
 // loader, the MFMA loop the consumer, the epilogue the storer; the epilogue of the reduce-scatter mode
@@ -18,6 +23,8 @@
 // compute workgroup itself).  In all-gather mode the workgroup does the `wait` on its chunk's flag
 // before its first load (section 3.1.3, inter-SM overlap seen from the compute side).
 #pragma once
+#include <type_traits>
+
 #include "pk_device.h"
 
 namespace pk {
@@ -39,7 +46,7 @@ struct GemmArgs {
     int32_t grp_tile_rows;
     int32_t n_groups;
     int32_t group0;
-    int32_t wg_per_group;     // 8 * ceil(grp_tile_rows * tiles_n / 8)
+    int32_t wg_per_group;     // 8 * ceil(grp_tile_rows * tiles_n / 8): tile slots of one group
     int32_t rank;
     // reduce-scatter epilogue
     float* partials;          // [P][rows_per_shard][n]
@@ -58,8 +65,31 @@ struct GemmArgs {
     uint64_t timeout_ticks;
 };
 
+constexpr int kEpiStageBytes = 32 * 1024;   // LDS staging of the epilogue, 8 KB per wave
+
 template <int BM, int BN>
-constexpr int gemm_lds_bytes() { return 2 * (BM * 128 + BN * 128); }
+constexpr int gemm_lds_bytes() { return 2 * (BM * 128 + BN * 128) + kEpiStageBytes; }
+
+// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
+#define PK_SG_MFMA 0x008
+#define PK_SG_VMEM 0x020
+#define PK_SG_DSRD 0x100
+
+// Ask the scheduler for: NM MFMAs with ND LDS reads and NV vector-memory loads spread evenly between them.
+template <int NM, int ND, int NV>
+__device__ __forceinline__ void interleave_hint() {
+#pragma unroll
+    for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(PK_SG_MFMA, 1, 0);
+        const int nd = (ND * (i + 1)) / NM - (ND * i) / NM;
+        const int nv = (NV * (i + 1)) / NM - (NV * i) / NM;
+        if (nd == 1) __builtin_amdgcn_sched_group_barrier(PK_SG_DSRD, 1, 0);
+        if (nd == 2) __builtin_amdgcn_sched_group_barrier(PK_SG_DSRD, 2, 0);
+        if (nd == 3) __builtin_amdgcn_sched_group_barrier(PK_SG_DSRD, 3, 0);
+        if (nv == 1) __builtin_amdgcn_sched_group_barrier(PK_SG_VMEM, 1, 0);
+        if (nv == 2) __builtin_amdgcn_sched_group_barrier(PK_SG_VMEM, 2, 0);
+    }
+}
 
 template <int BM, int BN, bool FP8, int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
@@ -75,8 +105,10 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
     constexpr int RPI = 64 / CPR;                        // B rows covered by one wave-wide load
     constexpr int NA = BM / 32, NB = BN / 32;            // wave-wide loads per thread per k-tile
     constexpr int KS = FP8 ? 2 : 4;                      // MFMA k-steps per k-tile
+    constexpr int NDS = FP8 ? (2 * TM + 4 * TN) : (TM + 2 * TN);   // LDS reads per k-step
     constexpr int BAND = 4;                              // tile rows swept column-major inside a group
     static_assert(CPR >= 8 && RPI >= 1, "tile too narrow");
+    typedef typename std::conditional<FP8, i32x8, bf16x8>::type frag_t;
 
     const int tid = threadIdx.x;
     const int l = tid & 63;
@@ -84,82 +116,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
     const int wm = w >> 1, wn = w & 1;
     const int h = l >> 5;
 
-    // ---- which tile (paper listing: interpret_task) ----
-    const int gi = blockIdx.x / g.wg_per_group;
-    const int u = blockIdx.x - gi * g.wg_per_group;
-    const int G = g.grp_tile_rows * g.tiles_n;
-    const int t = (u & 7) * (g.wg_per_group >> 3) + (u >> 3);
-    if (t >= G) return;
-    const int band = t / (BAND * g.tiles_n);
-    const int rem = t - band * BAND * g.tiles_n;
-    const int rows_in_band = min(BAND, g.grp_tile_rows - band * BAND);
-    const int tc = rem / rows_in_band;
-    const int tr = band * BAND + (rem - tc * rows_in_band);
-    int grp = g.group0 + gi;
-    if (grp >= g.n_groups) grp -= g.n_groups;
-    const int tile_row = grp * g.grp_tile_rows + tr;
-    const int q = tile_row / g.tiles_m_shard;            // destination rank (RS) / source chunk (AG)
-    const int tmi = tile_row - q * g.tiles_m_shard;
-    const int row0 = q * g.rows_per_shard + tmi * BM;
-    const int row_end = (q + 1) * g.rows_per_shard;
-    const int col0 = tc * BN;
-
-    // ---- all-gather: wait until the chunk this tile reads has landed ----
-    if constexpr (EPI == EPI_AG) {
-        if (q != g.rank) {
-            int late = 0;
-            if (tid == 0) {
-                late = flag_wait(g.chunk_flags + q, g.epoch, g.timeout_ticks) ? 0 : 1;
-                if (late) report_timeout(g.status, (uint32_t)q, 1u);
-            }
-            if (__syncthreads_or(late)) return;
-            acquire_agent();
-        }
-    }
-
-    // ---- per-lane global source addresses of the direct-to-LDS loads ----
-    const char* a_ptr[NA];
-    {
-        const int r_in = l >> 3, cp = l & 7;
-        const int gchunk = cp ^ (r_in ^ (w & 1));        // swizzle fA(r) = (r & 7) ^ ((r >> 3) & 1)
-#pragma unroll
-        for (int j = 0; j < NA; ++j) {
-            const int r = 32 * j + 8 * w + r_in;
-            const int grow = min(row0 + r, row_end - 1);
-            a_ptr[j] = g.A + (int64_t)grow * g.lda + gchunk * 16;
-        }
-    }
-    const char* b_ptr[NB];
-    {
-        const int kr_in = l / CPR, cp = l % CPR;
-        const int n_bytes = g.n * ELEM;
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const int kr = (j * 4 + w) * RPI + kr_in;
-            const int sw = FP8 ? 2 * ((kr & 7) % (CPR / 2))
-                               : 4 * (((kr & 3) | ((kr >> 1) & 4)) % (CPR / 4));
-            int colbyte = col0 * ELEM + (cp ^ sw) * 16;
-            if (colbyte >= n_bytes) colbyte = n_bytes - 16;   // edge tile: fetch valid memory, never stored
-            b_ptr[j] = g.B + (int64_t)kr * g.ldb + colbyte;
-        }
-    }
-    const int64_t b_step = (int64_t)B_ROWS * g.ldb;
-
-    auto issue_loads = [&](int stage) {
-        PK_LDS char* sa = lds + stage * STAGE + w * 1024;
-#pragma unroll
-        for (int j = 0; j < NA; ++j) {
-            __builtin_amdgcn_global_load_lds((PK_GLOBAL const void*)a_ptr[j], (PK_LDS void*)(sa + j * 4096), 16, 0, 0);
-            a_ptr[j] += 128;
-        }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            __builtin_amdgcn_global_load_lds((PK_GLOBAL const void*)b_ptr[j], (PK_LDS void*)(sa + A_BYTES + j * 4096), 16, 0, 0);
-            b_ptr[j] += b_step;
-        }
-    };
-
-    // ---- per-lane LDS fragment addresses ----
+    // ---- per-lane LDS fragment addresses (relative to a stage) ----
     const int fa = (l & 7) ^ ((l >> 3) & 1);
     const uint32_t a_row_off = (uint32_t)(wm * (BM / 2) + (l & 31)) * 128;
     const int s16 = l & 15, nhalf = (l >> 4) & 1;
@@ -182,133 +139,310 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
         }
     }
 
-    f32x16 acc[TM][TN];
+    // read the fragments of k-step kk of the k-tile held in LDS stage `st`
+    auto load_frags = [&](PK_LDS char* st, int kk, frag_t (&af)[TM], frag_t (&bfr)[TN]) {
+        if constexpr (!FP8) {
+            const uint32_t ao = a_row_off + (uint32_t)((((h ^ fa) ^ (2 * kk)) & 7) * 16);
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+            for (int ti = 0; ti < TM; ++ti) af[ti] = *(PK_LDS bf16x8*)(st + ao + ti * 4096);
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int tj = 0; tj < TN; ++tj) {
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk) * B_ROW_BYTES));
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk + 4) * B_ROW_BYTES));
+                s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                bfr[tj] = __builtin_bit_cast(bf16x8, both);
+            }
+        } else {
+            const uint32_t ao0 = a_row_off + (uint32_t)(((((2 * h) ^ fa) ^ (4 * kk)) & 7) * 16);
+            const uint32_t ao1 = a_row_off + (uint32_t)(((((2 * h + 1) ^ fa) ^ (4 * kk)) & 7) * 16);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    // ---- main loop: two LDS stages, one barrier per k-tile ----
-    issue_loads(0);
-    __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
-    __syncthreads();
-
-    for (int kt = 0; kt < g.ktiles; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < g.ktiles) issue_loads(cur ^ 1);
-        PK_LDS char* st = lds + cur * STAGE;
-
+            for (int ti = 0; ti < TM; ++ti) {
+                i32x4 x0 = *(PK_LDS i32x4*)(st + ao0 + ti * 4096);
+                i32x4 x1 = *(PK_LDS i32x4*)(st + ao1 + ti * 4096);
+                af[ti] = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
-        for (int kk = 0; kk < KS; ++kk) {
-            if constexpr (!FP8) {
-                bf16x8 af[TM], bfr[TN];
-                const uint32_t ao = a_row_off + (uint32_t)((((h ^ fa) ^ (2 * kk)) & 7) * 16);
+            for (int tj = 0; tj < TN; ++tj) {
+                i32x2 p[4];
 #pragma unroll
-                for (int ti = 0; ti < TM; ++ti)
-                    af[ti] = *(PK_LDS bf16x8*)(st + ao + ti * 4096);
-#pragma unroll
-                for (int tj = 0; tj < TN; ++tj) {
-                    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk) * B_ROW_BYTES));
-                    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk + 4) * B_ROW_BYTES));
-                    s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    bfr[tj] = __builtin_bit_cast(bf16x8, both);
-                }
-#pragma unroll
-                for (int ti = 0; ti < TM; ++ti)
-#pragma unroll
-                    for (int tj = 0; tj < TN; ++tj)
-                        acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tj], af[ti], acc[ti][tj], 0, 0, 0);
-            } else {
-                i32x8 af[TM], bfr[TN];
-                const uint32_t ao0 = a_row_off + (uint32_t)(((((2 * h) ^ fa) ^ (4 * kk)) & 7) * 16);
-                const uint32_t ao1 = a_row_off + (uint32_t)(((((2 * h + 1) ^ fa) ^ (4 * kk)) & 7) * 16);
-#pragma unroll
-                for (int ti = 0; ti < TM; ++ti) {
-                    i32x4 x0 = *(PK_LDS i32x4*)(st + ao0 + ti * 4096);
-                    i32x4 x1 = *(PK_LDS i32x4*)(st + ao1 + ti * 4096);
-                    af[ti] = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-#pragma unroll
-                for (int tj = 0; tj < TN; ++tj) {
-                    i32x2 p[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        p[r] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                            (PK_LDS i32x2*)(st + b_off[tj] + (64 * kk + 8 * r) * B_ROW_BYTES));
-                    i32x4 q0 = __builtin_shufflevector(p[0], p[1], 0, 1, 2, 3);
-                    i32x4 q1 = __builtin_shufflevector(p[2], p[3], 0, 1, 2, 3);
-                    bfr[tj] = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-#pragma unroll
-                for (int ti = 0; ti < TM; ++ti)
-#pragma unroll
-                    for (int tj = 0; tj < TN; ++tj)
-                        acc[ti][tj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            bfr[tj], af[ti], acc[ti][tj], 0, 0, 0, 0, 0, 0);
+                for (int r = 0; r < 4; ++r)
+                    p[r] = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+                        (PK_LDS i32x2*)(st + b_off[tj] + (64 * kk + 8 * r) * B_ROW_BYTES));
+                i32x4 q0 = __builtin_shufflevector(p[0], p[1], 0, 1, 2, 3);
+                i32x4 q1 = __builtin_shufflevector(p[2], p[3], 0, 1, 2, 3);
+                bfr[tj] = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
-        __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
-        __syncthreads();
-    }
+    };
 
-    // ---- epilogue (the storer): lane holds rows (l & 31), columns 8*b + 4*h + {0..3} of each 32x32 block ----
+    f32x16 acc[TM][TN];
+    auto mfma_step = [&](const frag_t (&af)[TM], const frag_t (&bfr)[TN]) {
+#pragma unroll
+        for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < TN; ++tj) {
+                if constexpr (!FP8)
+                    acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tj], af[ti], acc[ti][tj], 0, 0, 0);
+                else
+                    acc[ti][tj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[tj], af[ti], acc[ti][tj],
+                                                                                  0, 0, 0, 0, 0, 0);
+            }
+    };
+
+    // tile bookkeeping carried from one iteration to the next (the epilogue of a tile runs one iteration late)
+    int p_q = -1, p_tmi = 0, p_tc = 0, p_row0 = 0, p_row_end = 0, p_col0 = 0;
+    const int slots_total = g.wg_per_group * g.n_groups;
+    const int G = g.grp_tile_rows * g.tiles_n;
     float scale = 1.f;
     if constexpr (FP8) scale = g.scale_a[0] * g.scale_b[0];
-    const int row_l = row0 + wm * (BM / 2) + (l & 31);
-    const int col_l = col0 + wn * (BN / 2) + 4 * h;
 
-    if constexpr (EPI == EPI_RS) {
-        float* dst = (q == g.rank) ? g.partials + (int64_t)g.rank * g.slot_elems
-                                   : g.outgoing + (int64_t)q * g.slot_elems;
-        const int shard_row0 = q * g.rows_per_shard;
-#pragma unroll
-        for (int ti = 0; ti < TM; ++ti) {
-            const int row = row_l + ti * 32;
-            if (row < row_end) {
-                float* drow = dst + (int64_t)(row - shard_row0) * g.n;
-#pragma unroll
-                for (int tj = 0; tj < TN; ++tj)
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int col = col_l + tj * 32 + 8 * b;
-                        if (col < g.n) {
-                            f32x4 v = {acc[ti][tj][4 * b] * scale, acc[ti][tj][4 * b + 1] * scale,
-                                       acc[ti][tj][4 * b + 2] * scale, acc[ti][tj][4 * b + 3] * scale};
-                            *(f32x4*)(drow + col) = v;
-                        }
-                    }
+    auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
+        if constexpr (EPI == EPI_RS) {
+            if (tid == 0) {
+                uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
+                                                  : g.flags_out + (int64_t)p_q * g.flags_per_slot;
+                flag_signal(flags + (int64_t)p_tmi * g.tiles_n + p_tc, g.epoch);
             }
         }
-        // signal: every wave's stores are released at device scope before the flag is published
-        release_agent();
+    };
+
+    int v = blockIdx.x;
+    for (;;) {
+        // ---- which tile (paper listing: interpret_task) ----
+        int t = 0, gi = 0;
+        bool have = false;
+        while (v < slots_total) {
+            gi = v / g.wg_per_group;
+            const int u = v - gi * g.wg_per_group;
+            t = (u & 7) * (g.wg_per_group >> 3) + (u >> 3);
+            v += gridDim.x;
+            if (t < G) {
+                have = true;
+                break;
+            }
+        }
+        int q = 0, tmi = 0, tc = 0, row0 = 0, row_end = 0, col0 = 0;
+        uint32_t a_voff[NA], b_voff[NB];           // per-lane byte offsets from the k-tile base pointers
+        const char* a_base = g.A;                    // wave-uniform, advanced by one k-tile per issue
+        const char* b_base = g.B;
+        const int64_t b_step = (int64_t)B_ROWS * g.ldb;
+        if (have) {
+            const int band = t / (BAND * g.tiles_n);
+            const int rem = t - band * BAND * g.tiles_n;
+            const int rows_in_band = min(BAND, g.grp_tile_rows - band * BAND);
+            tc = rem / rows_in_band;
+            const int tr = band * BAND + (rem - tc * rows_in_band);
+            int grp = g.group0 + gi;
+            if (grp >= g.n_groups) grp -= g.n_groups;
+            const int tile_row = grp * g.grp_tile_rows + tr;
+            q = tile_row / g.tiles_m_shard;              // destination rank (RS) / source chunk (AG)
+            tmi = tile_row - q * g.tiles_m_shard;
+            row0 = q * g.rows_per_shard + tmi * BM;
+            row_end = (q + 1) * g.rows_per_shard;
+            col0 = tc * BN;
+
+            // all-gather: wait until the chunk this tile reads has landed
+            if constexpr (EPI == EPI_AG) {
+                if (q != g.rank) {
+                    // lane 0 polls; the verdict goes through a word of the (idle) epilogue staging area,
+                    // since the kernel leaves no LDS for a static variable
+                    PK_LDS int* verdict = (PK_LDS int*)(lds + 2 * STAGE);
+                    if (tid == 0) {
+                        const int late = flag_wait(g.chunk_flags + q, g.epoch, g.timeout_ticks) ? 0 : 1;
+                        if (late) report_timeout(g.status, (uint32_t)q, 1u);
+                        *verdict = late;
+                    }
+                    __syncthreads();
+                    const int late_all = *verdict;
+                    __syncthreads();
+                    if (late_all) have = false;                 // drain: this tile's rows stay untouched
+                    else acquire_agent();
+                }
+            }
+        }
+        if (have) {
+            // per-lane global source addresses of the direct-to-LDS loads
+            {
+                const int r_in = l >> 3, cp = l & 7;
+                const int gchunk = cp ^ (r_in ^ (w & 1));    // swizzle fA(r) = (r & 7) ^ ((r >> 3) & 1)
+#pragma unroll
+                for (int j = 0; j < NA; ++j) {
+                    const int r = 32 * j + 8 * w + r_in;
+                    const int grow = min(row0 + r, row_end - 1);
+                    a_voff[j] = (uint32_t)((int64_t)grow * g.lda + gchunk * 16);
+                }
+            }
+            {
+                const int kr_in = l / CPR, cp = l % CPR;
+                const int n_bytes = g.n * ELEM;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int kr = (j * 4 + w) * RPI + kr_in;
+                    const int sw = FP8 ? 2 * ((kr & 7) % (CPR / 2))
+                                       : 4 * (((kr & 3) | ((kr >> 1) & 4)) % (CPR / 4));
+                    int colbyte = col0 * ELEM + (cp ^ sw) * 16;
+                    if (colbyte >= n_bytes) colbyte = n_bytes - 16;   // edge tile: valid memory, never stored
+                    b_voff[j] = (uint32_t)((int64_t)kr * g.ldb + colbyte);
+                }
+            }
+        }
+        auto issue_loads = [&](int stage) {
+            PK_LDS char* sa = lds + stage * STAGE + w * 1024;
+#pragma unroll
+            for (int j = 0; j < NA; ++j)
+                __builtin_amdgcn_global_load_lds((PK_GLOBAL const void*)(a_base + a_voff[j]),
+                                                 (PK_LDS void*)(sa + j * 4096), 16, 0, 0);
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                __builtin_amdgcn_global_load_lds((PK_GLOBAL const void*)(b_base + b_voff[j]),
+                                                 (PK_LDS void*)(sa + A_BYTES + j * 4096), 16, 0, 0);
+            a_base += 128;
+            b_base += b_step;
+        };
+        // the LDS stages are free here: every wave passed the last barrier of the previous tile's loop
+        // after its final fragment reads were issued and waited for
+        if (have) {
+            issue_loads(0);
+            if (g.ktiles > 1) issue_loads(1);
+        }
+
+        // ---- epilogue of the previous tile (the storer), under the latency of the loads just issued ----
+        if (p_q >= 0) {
+            // lane holds, for each 32x32 block, rows (l & 31) and columns 8*b + 4*h + {0..3}.  Per pass one row
+            // of blocks (32 rows x BN/2 columns) goes through the wave's private staging area, then out as whole
+            // row segments, 16 bytes per lane.
+            PK_LDS char* stg = lds + 2 * STAGE + w * (kEpiStageBytes / 4);
+            constexpr int WCOLS = BN / 2;                    // columns of the wave's sub-tile
+            constexpr int OUT_ELEM = (EPI == EPI_RS) ? 4 : 2;
+            constexpr int ROW_BYTES = WCOLS * OUT_ELEM;      // 512 (fp32, BN=256) ... 128 (bf16, BN=128)
+            constexpr int ROWS_PASS = (kEpiStageBytes / 4) / ROW_BYTES >= 32 ? 32 : (kEpiStageBytes / 4) / ROW_BYTES;
+            static_assert(ROWS_PASS == 32 || ROWS_PASS == 16, "staging area too small");
+            constexpr int CH = ROW_BYTES / 16;               // 16-byte chunks per staged row
+            constexpr int LANES_ROW = CH;                    // lanes that cover one row on the way out
+            constexpr int ROWS_INSTR = 64 / LANES_ROW;       // rows written by one wave-wide store
+            const int col_w0 = p_col0 + wn * WCOLS;
+            char* dst_base;
+            int64_t dst_pitch;
+            int dst_row0;                                    // global row -> row inside the destination
+            if constexpr (EPI == EPI_RS) {
+                float* d = (p_q == g.rank) ? g.partials + (int64_t)g.rank * g.slot_elems
+                                           : g.outgoing + (int64_t)p_q * g.slot_elems;
+                dst_base = (char*)d;
+                dst_pitch = (int64_t)g.n * 4;
+                dst_row0 = p_q * g.rows_per_shard;
+            } else {
+                dst_base = (char*)g.C;
+                dst_pitch = (int64_t)g.n * 2;
+                dst_row0 = 0;
+            }
+#pragma unroll
+            for (int ti = 0; ti < TM; ++ti) {
+#pragma unroll
+                for (int half = 0; half < 32 / ROWS_PASS; ++half) {
+                    // write: lanes whose row falls in this pass store their quads; chunk position swizzled by row
+                    const int rl = l & 31;
+                    if (ROWS_PASS == 32 || (rl / ROWS_PASS) == half) {
+                        const int rs = rl % ROWS_PASS;
+#pragma unroll
+                        for (int tj = 0; tj < TN; ++tj)
+#pragma unroll
+                            for (int b = 0; b < 4; ++b) {
+                                const int colw = tj * 32 + 8 * b + 4 * h;     // column inside the wave sub-tile
+                                if constexpr (EPI == EPI_RS) {
+                                    const int ch = colw >> 2;                  // 16-byte chunk (4 floats)
+                                    f32x4 val = {acc[ti][tj][4 * b] * scale, acc[ti][tj][4 * b + 1] * scale,
+                                                 acc[ti][tj][4 * b + 2] * scale, acc[ti][tj][4 * b + 3] * scale};
+                                    *(PK_LDS f32x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16)) = val;
+                                } else {
+                                    const int ch = colw >> 3;                  // 16-byte chunk (8 bf16)
+                                    bf16x4 val = {(__bf16)(acc[ti][tj][4 * b] * scale), (__bf16)(acc[ti][tj][4 * b + 1] * scale),
+                                                  (__bf16)(acc[ti][tj][4 * b + 2] * scale), (__bf16)(acc[ti][tj][4 * b + 3] * scale)};
+                                    *(PK_LDS bf16x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16) + (h * 8)) = val;
+                                }
+                            }
+                    }
+                    // read back row-wise and store: lane -> (row = i*ROWS_INSTR + l / LANES_ROW, chunk = l % LANES_ROW)
+#pragma unroll
+                    for (int i = 0; i < ROWS_PASS / ROWS_INSTR; ++i) {
+                        const int rs = i * ROWS_INSTR + l / LANES_ROW;
+                        const int ch = l % LANES_ROW;
+                        i32x4 val = *(PK_LDS i32x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16));
+                        const int row = p_row0 + wm * (BM / 2) + ti * 32 + half * ROWS_PASS + rs;
+                        const int col = col_w0 + ch * (16 / OUT_ELEM);
+                        if (row < p_row_end && col < g.n)
+                            __builtin_nontemporal_store(val, (i32x4*)(dst_base + (int64_t)(row - dst_row0) * dst_pitch +
+                                                                      (int64_t)col * OUT_ELEM));
+                    }
+                }
+            }
+        }
+        if (!have) break;
+
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+        // first k-tile(s) landed; the previous tile's stores (same counter) are complete as well
+        __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
         __syncthreads();
-        if (tid == 0) {
-            uint32_t* flags = (q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
-                                            : g.flags_out + (int64_t)q * g.flags_per_slot;
-            flag_signal(flags + (int64_t)tmi * g.tiles_n + tc, g.epoch);
-        }
-    } else {
+        if (p_q >= 0) signal_prev();
+
+        // ---- main loop ----
+        frag_t af0[TM], bf0[TN], af1[TM], bf1[TN];
+        load_frags(lds, 0, af0, bf0);
+        // one k-tile: KS-1 pipelined k-steps, the barrier, then the last k-step under which the loads of
+        // k-tile kt+2 (LOADS) and the first fragments of k-tile kt+1 (NEXT) are issued
+        auto ktile = [&](int kt, auto loads_c, auto next_c) {
+            constexpr bool LOADS = decltype(loads_c)::value, NEXT = decltype(next_c)::value;
+            PK_LDS char* st = lds + (kt & 1) * STAGE;
+            PK_LDS char* nx = lds + ((kt & 1) ^ 1) * STAGE;
 #pragma unroll
-        for (int ti = 0; ti < TM; ++ti) {
-            const int row = row_l + ti * 32;
-            if (row < row_end) {
-                uint16_t* drow = g.C + (int64_t)row * g.n;
-#pragma unroll
-                for (int tj = 0; tj < TN; ++tj)
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int col = col_l + tj * 32 + 8 * b;
-                        if (col < g.n) {
-                            bf16x4 v = {(__bf16)(acc[ti][tj][4 * b] * scale), (__bf16)(acc[ti][tj][4 * b + 1] * scale),
-                                        (__bf16)(acc[ti][tj][4 * b + 2] * scale), (__bf16)(acc[ti][tj][4 * b + 3] * scale)};
-                            *(bf16x4*)(drow + col) = v;
-                        }
-                    }
+            for (int kk = 0; kk < KS - 1; ++kk) {
+                if (kk & 1) {
+                    load_frags(st, kk + 1, af0, bf0);
+                    mfma_step(af1, bf1);
+                } else {
+                    load_frags(st, kk + 1, af1, bf1);
+                    mfma_step(af0, bf0);
+                }
+                interleave_hint<TM * TN, NDS, 0>();
+                __builtin_amdgcn_sched_barrier(0);
             }
+            // k-tile kt+1 has landed (it was issued a whole k-tile ago) and nobody reads this stage any more
+            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+            __syncthreads();
+            if constexpr (LOADS) issue_loads(kt & 1);
+            if constexpr (NEXT) load_frags(nx, 0, af0, bf0);
+            mfma_step(af1, bf1);
+            interleave_hint<TM * TN, NEXT ? NDS : 0, LOADS ? NA + NB : 0>();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        {
+            int kt = 0;
+            for (; kt + 2 < g.ktiles; ++kt) ktile(kt, std::true_type{}, std::true_type{});
+            if (g.ktiles >= 2) ktile(g.ktiles - 2, std::false_type{}, std::true_type{});
+            ktile(g.ktiles - 1, std::false_type{}, std::false_type{});
+        }
+
+        p_q = q;
+        p_tmi = tmi;
+        p_tc = tc;
+        p_row0 = row0;
+        p_row_end = row_end;
+        p_col0 = col0;
+    }
+
+    // the last tile's stores: release at device scope in every wave, then publish its flag
+    if constexpr (EPI == EPI_RS) {
+        if (p_q >= 0) {
+            release_agent();
+            __syncthreads();
+            signal_prev();
         }
     }
 }

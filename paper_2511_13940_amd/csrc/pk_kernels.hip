@@ -172,6 +172,8 @@ static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt,
     const int kt = dt == PK_FP8_E4M3 ? 128 : 64, nv = dt == PK_FP8_E4M3 ? 16 : 8;
     if (k % kt || n % nv) return PK_ERR_SHAPE;
     if (m > (1 << 30) || n > (1 << 30) || k > (1 << 30)) return PK_ERR_SHAPE;
+    // the kernels address each operand with 32-bit byte offsets from its base
+    if (m * k * 2 >= ((int64_t)1 << 32) || k * n * 2 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
     *lm = m;
     *ln = n;
     *lk = k;
