@@ -57,6 +57,17 @@ __device__ __forceinline__ void report_timeout(uint32_t* status, uint32_t index,
     }
 }
 
+// 16-byte-per-lane direct-to-LDS load: lane l's 16 bytes from (sbase + voff) land at LDS byte address lds_addr + 16*l.
+// Written as inline assembly on purpose: for the builtin form the compiler cannot tell which LDS bytes the load
+// writes and makes every later LDS read wait for it (vmcnt(0)), which serialises the pipeline.  The kernel waits
+// for these loads itself (s_waitcnt vmcnt + workgroup barrier) before any wave reads what they wrote.
+__device__ __forceinline__ void dma_load16(const char* sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(voff), "s"(sbase)
+                 : "m0");
+}
+
 __device__ __forceinline__ void acquire_agent() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 __device__ __forceinline__ void release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 

@@ -1,17 +1,18 @@
 // The MFMA GEMM kernel behind pk_gemm_rs and pk_ag_gemm (gfx950 only).
 //
-// A persistent workgroup of 4 waves (2 x 2) walks over BM x BN tiles of the local product; each wave owns a
-// (BM/2) x (BN/2) sub-tile as (BM/64) x (BN/64) accumulators of the 32x32 MFMA.  Per k-tile of 128 bytes
-// of A-row (64 bf16 or 128 fp8):
-//   * the A tile (BM x 128 B) and B tile (128*BN B) are copied global -> LDS with 16-byte direct-to-LDS
-//     loads (no VGPR staging) one k-tile ahead, into the LDS stage that is not being read (two stages);
+// A persistent workgroup of WM x WN waves walks over BM x BN tiles of the local product; each wave owns a
+// (BM/WM) x (BN/WN) sub-tile as 32x32 MFMA accumulators.  The reduction runs in k-tiles of KB bytes of
+// A-row (KB = 64 or 128: 32 or 64 bf16, 64 or 128 fp8):
+//   * the A tile (BM x KB bytes) and B tile (KB*BN bytes) are copied global -> LDS with 16-byte
+//     direct-to-LDS loads (no VGPR staging) into a ring of NS LDS stages, NS-1 k-tiles ahead of their use,
+//     so that the loads of a k-tile have NS-1 k-tiles of time to land and are issued a few per k-tile;
 //   * A fragments are read with ds_read_b128, B fragments with the transposing ds_read_b64_tr_b16 /
 //     _tr_b8 (B is row-major K x N, the MFMA wants k-contiguous lanes);
 //   * both LDS tiles are XOR-swizzled at 16-byte-chunk granularity; a direct-to-LDS load writes lane l's
 //     16 bytes at base + 16*l, so the swizzle is applied by choosing which global chunk each lane fetches;
 //   * the loop is software-pipelined: the fragments of k-step s+1 are read while the MFMAs of step s issue,
-//     and the single barrier of a k-tile sits before its last k-step, so the next tile's loads and the
-//     first fragments of the next k-tile are issued under that step's MFMAs.
+//     and the single barrier of a k-tile sits before its last k-step, so the loads of a later k-tile and
+//     the first fragments of the next k-tile are issued under that step's MFMAs.
 // The operands are passed to the MFMA swapped (B fragment first), which leaves each lane with four
 // consecutive columns of one row; the epilogue transposes through a 32 KB LDS staging area so that global
 // stores are 16 bytes per lane over whole row segments of the wave's sub-tile.  The epilogue of tile t runs
@@ -36,7 +37,7 @@ struct GemmArgs {
     const char* B;            // local second operand, row-major
     int64_t lda, ldb;         // bytes per row
     int32_t n;                // columns of the local product
-    int32_t ktiles;           // local k / (elements per 128-byte k-tile)
+    int32_t ktiles;           // local k in k-tiles of KB bytes of A-row
     // tile space: (P * tiles_m_shard) x tiles_n; a tile never crosses a multiple of rows_per_shard
     int32_t rows_per_shard;   // M/P
     int32_t tiles_m_shard;    // ceil(rows_per_shard / BM)
@@ -65,60 +66,53 @@ struct GemmArgs {
     uint64_t timeout_ticks;
 };
 
-constexpr int kEpiStageBytes = 32 * 1024;   // LDS staging of the epilogue, 8 KB per wave
+constexpr int kEpiStageBytes = 32 * 1024;   // LDS staging of the epilogue, shared out evenly to the waves
 
-template <int BM, int BN>
-constexpr int gemm_lds_bytes() { return 2 * (BM * 128 + BN * 128) + kEpiStageBytes; }
+template <int BM, int BN, int KB, int NS>
+constexpr int gemm_lds_bytes() { return NS * (BM + BN) * KB + kEpiStageBytes; }
 
-// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
-#define PK_SG_MFMA 0x008
-#define PK_SG_VMEM 0x020
-#define PK_SG_DSRD 0x100
+// s_waitcnt immediate for vmcnt(N) lgkmcnt(0) (gfx9 encoding, expcnt left alone)
+constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-// Ask the scheduler for: NM MFMAs with ND LDS reads and NV vector-memory loads spread evenly between them.
-template <int NM, int ND, int NV>
-__device__ __forceinline__ void interleave_hint() {
-#pragma unroll
-    for (int i = 0; i < NM; ++i) {
-        __builtin_amdgcn_sched_group_barrier(PK_SG_MFMA, 1, 0);
-        const int nd = (ND * (i + 1)) / NM - (ND * i) / NM;
-        const int nv = (NV * (i + 1)) / NM - (NV * i) / NM;
-        if (nd == 1) __builtin_amdgcn_sched_group_barrier(PK_SG_DSRD, 1, 0);
-        if (nd == 2) __builtin_amdgcn_sched_group_barrier(PK_SG_DSRD, 2, 0);
-        if (nd == 3) __builtin_amdgcn_sched_group_barrier(PK_SG_DSRD, 3, 0);
-        if (nv == 1) __builtin_amdgcn_sched_group_barrier(PK_SG_VMEM, 1, 0);
-        if (nv == 2) __builtin_amdgcn_sched_group_barrier(PK_SG_VMEM, 2, 0);
-    }
-}
-
-template <int BM, int BN, bool FP8, int EPI>
-__global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
+__global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     PK_LDS char* lds = (PK_LDS char*)smem_generic;
 
-    constexpr int TM = BM / 64, TN = BN / 64;           // 32x32 accumulators per wave: TM x TN
-    constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+    constexpr int NW = WM * WN;                          // waves per workgroup
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 accumulators per wave: TM x TN
+    constexpr int A_BYTES = BM * KB, B_BYTES = BN * KB, STAGE = A_BYTES + B_BYTES;
     constexpr int ELEM = FP8 ? 1 : 2;
-    constexpr int B_ROWS = FP8 ? 128 : 64;               // k-rows in a B tile
+    constexpr int CPA = KB / 16;                         // 16-byte chunks per A tile row (8 or 4)
+    constexpr int B_ROWS = KB / ELEM;                    // k-rows in a B tile
     constexpr int B_ROW_BYTES = BN * ELEM;
     constexpr int CPR = B_ROW_BYTES / 16;                // 16-byte chunks per B tile row
     constexpr int RPI = 64 / CPR;                        // B rows covered by one wave-wide load
-    constexpr int NA = BM / 32, NB = BN / 32;            // wave-wide loads per thread per k-tile
-    constexpr int KS = FP8 ? 2 : 4;                      // MFMA k-steps per k-tile
-    constexpr int NDS = FP8 ? (2 * TM + 4 * TN) : (TM + 2 * TN);   // LDS reads per k-step
+    constexpr int NA = A_BYTES / 1024 / NW, NB = B_BYTES / 1024 / NW;   // wave-wide loads per wave per k-tile
+    constexpr int NL = NA + NB;
+    constexpr int KS = FP8 ? KB / 64 : KB / 32;          // MFMA k-steps per k-tile
     constexpr int BAND = 4;                              // tile rows swept column-major inside a group
+    constexpr int EPI_OFF = NS * STAGE;                  // LDS offset of the epilogue staging area
+    static_assert(KB == 64 || KB == 128, "k-tile is 64 or 128 bytes of A row");
+    static_assert(KS >= 2 && KS % 2 == 0, "the fragment double buffer needs an even number of k-steps");
     static_assert(CPR >= 8 && RPI >= 1, "tile too narrow");
+    static_assert(NW % 2 == 0 && NA >= 1 && NB >= 1, "wave grid does not fit the tile");
+    static_assert((NS - 2) * NL <= 63, "too many loads in flight for the counter");
     typedef typename std::conditional<FP8, i32x8, bf16x8>::type frag_t;
 
     const int tid = threadIdx.x;
     const int l = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;
+    const int wm = w / WN, wn = w % WN;
     const int h = l >> 5;
 
+    // A-tile swizzle: LDS chunk position = k-chunk ^ fA(row).
+    //   128-byte rows: fA(r) = (r & 7) ^ ((r >> 3) & 1);  64-byte rows: fA(r) = ((r >> 1) & 3) ^ ((r >> 3) & 1)
+    auto fA = [](int r) { return KB == 128 ? ((r & 7) ^ ((r >> 3) & 1)) : (((r >> 1) & 3) ^ ((r >> 3) & 1)); };
+
     // ---- per-lane LDS fragment addresses (relative to a stage) ----
-    const int fa = (l & 7) ^ ((l >> 3) & 1);
-    const uint32_t a_row_off = (uint32_t)(wm * (BM / 2) + (l & 31)) * 128;
+    const int fa = fA(l & 31);                           // rows of a fragment differ from (l & 31) by multiples of 32
+    const uint32_t a_row_off = (uint32_t)(wm * (BM / WM) + (l & 31)) * KB;
     const int s16 = l & 15, nhalf = (l >> 4) & 1;
     uint32_t b_off[TN];
     if constexpr (!FP8) {
@@ -126,7 +120,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
         const int gsw = ((s16 >> 2) | (h << 2)) % (CPR / 4);
 #pragma unroll
         for (int tj = 0; tj < TN; ++tj) {
-            const int c = wn * (BN / 16) + tj * 4 + 2 * nhalf + ((s16 & 3) >> 1);
+            const int c = wn * (BN / WN / 8) + tj * 4 + 2 * nhalf + ((s16 & 3) >> 1);
             b_off[tj] = (uint32_t)(A_BYTES + krow_base * B_ROW_BYTES + (c ^ (4 * gsw)) * 16 + (s16 & 1) * 8);
         }
     } else {
@@ -134,37 +128,32 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
         const int gsw = ((s16 >> 1) & 7) % (CPR / 2);
 #pragma unroll
         for (int tj = 0; tj < TN; ++tj) {
-            const int c = wn * (BN / 32) + tj * 2 + nhalf;
+            const int c = wn * (BN / WN / 16) + tj * 2 + nhalf;
             b_off[tj] = (uint32_t)(A_BYTES + krow_base * B_ROW_BYTES + (c ^ (2 * gsw)) * 16 + (s16 & 1) * 8);
         }
     }
 
-    // read the fragments of k-step kk of the k-tile held in LDS stage `st`
-    auto load_frags = [&](PK_LDS char* st, int kk, frag_t (&af)[TM], frag_t (&bfr)[TN]) {
+    // Fragment reads of k-step kk of the k-tile held in LDS stage `st`, as NU = TN + TM units in the order the
+    // MFMAs need them: B fragments first, then A fragments.
+    constexpr int NU = TN + TM;
+    auto read_unit = [&](PK_LDS char* st, int kk, int u, frag_t (&af)[TM], frag_t (&bfr)[TN]) {
         if constexpr (!FP8) {
-            const uint32_t ao = a_row_off + (uint32_t)((((h ^ fa) ^ (2 * kk)) & 7) * 16);
-#pragma unroll
-            for (int ti = 0; ti < TM; ++ti) af[ti] = *(PK_LDS bf16x8*)(st + ao + ti * 4096);
-#pragma unroll
-            for (int tj = 0; tj < TN; ++tj) {
+            if (u < TN) {
+                const int tj = u;
                 s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk) * B_ROW_BYTES));
                 s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk + 4) * B_ROW_BYTES));
                 s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 bfr[tj] = __builtin_bit_cast(bf16x8, both);
+            } else {
+                const int ti = u - TN;
+                const uint32_t ao = a_row_off + (uint32_t)((((2 * kk + h) ^ fa) & (CPA - 1)) * 16);
+                af[ti] = *(PK_LDS bf16x8*)(st + ao + ti * 32 * KB);
             }
         } else {
-            const uint32_t ao0 = a_row_off + (uint32_t)(((((2 * h) ^ fa) ^ (4 * kk)) & 7) * 16);
-            const uint32_t ao1 = a_row_off + (uint32_t)(((((2 * h + 1) ^ fa) ^ (4 * kk)) & 7) * 16);
-#pragma unroll
-            for (int ti = 0; ti < TM; ++ti) {
-                i32x4 x0 = *(PK_LDS i32x4*)(st + ao0 + ti * 4096);
-                i32x4 x1 = *(PK_LDS i32x4*)(st + ao1 + ti * 4096);
-                af[ti] = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-#pragma unroll
-            for (int tj = 0; tj < TN; ++tj) {
+            if (u < TN) {
+                const int tj = u;
                 i32x2 p[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
@@ -173,22 +162,27 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
                 i32x4 q0 = __builtin_shufflevector(p[0], p[1], 0, 1, 2, 3);
                 i32x4 q1 = __builtin_shufflevector(p[2], p[3], 0, 1, 2, 3);
                 bfr[tj] = __builtin_shufflevector(q0, q1, 0, 1, 2, 3, 4, 5, 6, 7);
+            } else {
+                const int ti = u - TN;
+                const uint32_t ao0 = a_row_off + (uint32_t)((((4 * kk + 2 * h) ^ fa) & (CPA - 1)) * 16);
+                const uint32_t ao1 = a_row_off + (uint32_t)((((4 * kk + 2 * h + 1) ^ fa) & (CPA - 1)) * 16);
+                i32x4 x0 = *(PK_LDS i32x4*)(st + ao0 + ti * 32 * KB);
+                i32x4 x1 = *(PK_LDS i32x4*)(st + ao1 + ti * 32 * KB);
+                af[ti] = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7);
             }
         }
     };
+    auto load_frags = [&](PK_LDS char* st, int kk, frag_t (&af)[TM], frag_t (&bfr)[TN]) {
+#pragma unroll
+        for (int u = 0; u < NU; ++u) read_unit(st, kk, u, af, bfr);
+    };
 
     f32x16 acc[TM][TN];
-    auto mfma_step = [&](const frag_t (&af)[TM], const frag_t (&bfr)[TN]) {
-#pragma unroll
-        for (int ti = 0; ti < TM; ++ti)
-#pragma unroll
-            for (int tj = 0; tj < TN; ++tj) {
-                if constexpr (!FP8)
-                    acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tj], af[ti], acc[ti][tj], 0, 0, 0);
-                else
-                    acc[ti][tj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[tj], af[ti], acc[ti][tj],
-                                                                                  0, 0, 0, 0, 0, 0);
-            }
+    auto mfma_one = [&](int ti, int tj, const frag_t (&af)[TM], const frag_t (&bfr)[TN]) {
+        if constexpr (!FP8)
+            acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[tj], af[ti], acc[ti][tj], 0, 0, 0);
+        else
+            acc[ti][tj] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(bfr[tj], af[ti], acc[ti][tj], 0, 0, 0, 0, 0, 0);
     };
 
     // tile bookkeeping carried from one iteration to the next (the epilogue of a tile runs one iteration late)
@@ -248,7 +242,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
                 if (q != g.rank) {
                     // lane 0 polls; the verdict goes through a word of the (idle) epilogue staging area,
                     // since the kernel leaves no LDS for a static variable
-                    PK_LDS int* verdict = (PK_LDS int*)(lds + 2 * STAGE);
+                    PK_LDS int* verdict = (PK_LDS int*)(lds + EPI_OFF);
                     if (tid == 0) {
                         const int late = flag_wait(g.chunk_flags + q, g.epoch, g.timeout_ticks) ? 0 : 1;
                         if (late) report_timeout(g.status, (uint32_t)q, 1u);
@@ -263,15 +257,15 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
             }
         }
         if (have) {
-            // per-lane global source addresses of the direct-to-LDS loads
+            // per-lane global source addresses of the direct-to-LDS loads.  Wave-wide load j of wave w fills
+            // the 1 KB LDS block j*NW + w of the A (or B) tile.
             {
-                const int r_in = l >> 3, cp = l & 7;
-                const int gchunk = cp ^ (r_in ^ (w & 1));    // swizzle fA(r) = (r & 7) ^ ((r >> 3) & 1)
+                const int r_in = l / CPA, cp = l % CPA;
 #pragma unroll
                 for (int j = 0; j < NA; ++j) {
-                    const int r = 32 * j + 8 * w + r_in;
+                    const int r = (64 / CPA) * (j * NW + w) + r_in;
                     const int grow = min(row0 + r, row_end - 1);
-                    a_voff[j] = (uint32_t)((int64_t)grow * g.lda + gchunk * 16);
+                    a_voff[j] = (uint32_t)((int64_t)grow * g.lda + (cp ^ fA(r)) * 16);
                 }
             }
             {
@@ -279,7 +273,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
                 const int n_bytes = g.n * ELEM;
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
-                    const int kr = (j * 4 + w) * RPI + kr_in;
+                    const int kr = (j * NW + w) * RPI + kr_in;
                     const int sw = FP8 ? 2 * ((kr & 7) % (CPR / 2))
                                        : 4 * (((kr & 3) | ((kr >> 1) & 4)) % (CPR / 4));
                     int colbyte = col0 * ELEM + (cp ^ sw) * 16;
@@ -288,37 +282,40 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
                 }
             }
         }
+        // load number i (0 .. NL-1) of this wave for the next k-tile to fetch, into LDS stage `stage`
+        const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+        auto issue_load = [&](int stage, int i) {
+            const uint32_t sa = lds_base + stage * STAGE + w * 1024;
+            if (i < NA) dma_load16(a_base, a_voff[i], sa + i * NW * 1024);
+            else dma_load16(b_base, b_voff[i - NA], sa + A_BYTES + (i - NA) * NW * 1024);
+            if (i == NL - 1) {
+                a_base += KB;
+                b_base += b_step;
+            }
+        };
         auto issue_loads = [&](int stage) {
-            PK_LDS char* sa = lds + stage * STAGE + w * 1024;
 #pragma unroll
-            for (int j = 0; j < NA; ++j)
-                __builtin_amdgcn_global_load_lds((PK_GLOBAL const void*)(a_base + a_voff[j]),
-                                                 (PK_LDS void*)(sa + j * 4096), 16, 0, 0);
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-                __builtin_amdgcn_global_load_lds((PK_GLOBAL const void*)(b_base + b_voff[j]),
-                                                 (PK_LDS void*)(sa + A_BYTES + j * 4096), 16, 0, 0);
-            a_base += 128;
-            b_base += b_step;
+            for (int i = 0; i < NL; ++i) issue_load(stage, i);
         };
         // the LDS stages are free here: every wave passed the last barrier of the previous tile's loop
         // after its final fragment reads were issued and waited for
         if (have) {
-            issue_loads(0);
-            if (g.ktiles > 1) issue_loads(1);
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                if (s < g.ktiles) issue_loads(s);
         }
 
         // ---- epilogue of the previous tile (the storer), under the latency of the loads just issued ----
         if (p_q >= 0) {
-            // lane holds, for each 32x32 block, rows (l & 31) and columns 8*b + 4*h + {0..3}.  Per pass one row
-            // of blocks (32 rows x BN/2 columns) goes through the wave's private staging area, then out as whole
+            // lane holds, for each 32x32 block, rows (l & 31) and columns 8*b + 4*h + {0..3}.  Per pass a slab of
+            // ROWS_PASS rows x (BN/WN) columns goes through the wave's private staging area, then out as whole
             // row segments, 16 bytes per lane.
-            PK_LDS char* stg = lds + 2 * STAGE + w * (kEpiStageBytes / 4);
-            constexpr int WCOLS = BN / 2;                    // columns of the wave's sub-tile
+            PK_LDS char* stg = lds + EPI_OFF + w * (kEpiStageBytes / NW);
+            constexpr int WCOLS = BN / WN;                   // columns of the wave's sub-tile
             constexpr int OUT_ELEM = (EPI == EPI_RS) ? 4 : 2;
-            constexpr int ROW_BYTES = WCOLS * OUT_ELEM;      // 512 (fp32, BN=256) ... 128 (bf16, BN=128)
-            constexpr int ROWS_PASS = (kEpiStageBytes / 4) / ROW_BYTES >= 32 ? 32 : (kEpiStageBytes / 4) / ROW_BYTES;
-            static_assert(ROWS_PASS == 32 || ROWS_PASS == 16, "staging area too small");
+            constexpr int ROW_BYTES = WCOLS * OUT_ELEM;
+            constexpr int ROWS_PASS = (kEpiStageBytes / NW) / ROW_BYTES >= 32 ? 32 : (kEpiStageBytes / NW) / ROW_BYTES;
+            static_assert(ROWS_PASS == 32 || ROWS_PASS == 16 || ROWS_PASS == 8, "staging area too small");
             constexpr int CH = ROW_BYTES / 16;               // 16-byte chunks per staged row
             constexpr int LANES_ROW = CH;                    // lanes that cover one row on the way out
             constexpr int ROWS_INSTR = 64 / LANES_ROW;       // rows written by one wave-wide store
@@ -369,7 +366,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
                         const int rs = i * ROWS_INSTR + l / LANES_ROW;
                         const int ch = l % LANES_ROW;
                         i32x4 val = *(PK_LDS i32x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16));
-                        const int row = p_row0 + wm * (BM / 2) + ti * 32 + half * ROWS_PASS + rs;
+                        const int row = p_row0 + wm * (BM / WM) + ti * 32 + half * ROWS_PASS + rs;
                         const int col = col_w0 + ch * (16 / OUT_ELEM);
                         if (row < p_row_end && col < g.n)
                             __builtin_nontemporal_store(val, (i32x4*)(dst_base + (int64_t)(row - dst_row0) * dst_pitch +
@@ -387,7 +384,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-        // first k-tile(s) landed; the previous tile's stores (same counter) are complete as well
+        // the first k-tiles have landed; the previous tile's stores (same counter) are complete as well
         __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
         __syncthreads();
         if (p_q >= 0) signal_prev();
@@ -395,38 +392,56 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const GemmArgs g) {
         // ---- main loop ----
         frag_t af0[TM], bf0[TN], af1[TM], bf1[TN];
         load_frags(lds, 0, af0, bf0);
-        // one k-tile: KS-1 pipelined k-steps, the barrier, then the last k-step under which the loads of
-        // k-tile kt+2 (LOADS) and the first fragments of k-tile kt+1 (NEXT) are issued
-        auto ktile = [&](int kt, auto loads_c, auto next_c) {
-            constexpr bool LOADS = decltype(loads_c)::value, NEXT = decltype(next_c)::value;
-            PK_LDS char* st = lds + (kt & 1) * STAGE;
-            PK_LDS char* nx = lds + ((kt & 1) ^ 1) * STAGE;
+        // One k-tile: KS-1 pipelined k-steps, the barrier, then the last k-step, under which the loads of
+        // k-tile kt+NS (LOADS) and the first fragments of k-tile kt+1 (NEXT) are issued.  At the barrier every
+        // wave has finished reading k-tile kt's stage, so it can be refilled, and k-tile kt+1 has landed: in the
+        // steady state only the loads of the NS-2 k-tiles after it may still be in flight.
+        // One k-step: the NM MFMAs on fragment set (ca, cb), with, pinned between them in this order, the reads
+        // of the next step's fragments into (na, nb) behind the first half of the MFMAs (they then have the
+        // second half of the step to arrive) and the direct-to-LDS loads of a later k-tile behind the second half.
+        auto kstep = [&](const frag_t (&ca)[TM], const frag_t (&cb)[TN], frag_t (&na)[TM], frag_t (&nb)[TN],
+                         PK_LDS char* rd_stage, int rd_kk, auto reads_c, int ld_stage, auto loads_c) {
+            constexpr bool READS = decltype(reads_c)::value, LOADS = decltype(loads_c)::value;
+            constexpr int NM = TM * TN, H = NM / 2;
 #pragma unroll
-            for (int kk = 0; kk < KS - 1; ++kk) {
-                if (kk & 1) {
-                    load_frags(st, kk + 1, af0, bf0);
-                    mfma_step(af1, bf1);
-                } else {
-                    load_frags(st, kk + 1, af1, bf1);
-                    mfma_step(af0, bf0);
+            for (int i = 0; i < NM; ++i) {
+                mfma_one(i / TN, i % TN, ca, cb);
+                if constexpr (READS) {
+                    if (i < H) {
+#pragma unroll
+                        for (int u = (NU * i) / H; u < (NU * (i + 1)) / H; ++u) read_unit(rd_stage, rd_kk, u, na, nb);
+                    }
                 }
-                interleave_hint<TM * TN, NDS, 0>();
+                if constexpr (LOADS) {
+                    if (i >= NM - H) {
+#pragma unroll
+                        for (int x = (NL * (i - (NM - H))) / H; x < (NL * (i - (NM - H) + 1)) / H; ++x)
+                            issue_load(ld_stage, x);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // k-tile kt+1 has landed (it was issued a whole k-tile ago) and nobody reads this stage any more
-            __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+        };
+        auto ktile = [&](int kt, auto loads_c, auto next_c) {
+            constexpr bool LOADS = decltype(loads_c)::value;
+            const int sidx = kt % NS;
+            PK_LDS char* st = lds + sidx * STAGE;
+            PK_LDS char* nx = lds + (sidx + 1 == NS ? 0 : sidx + 1) * STAGE;
+#pragma unroll
+            for (int kk = 0; kk < KS - 1; ++kk) {
+                if (kk & 1) kstep(af1, bf1, af0, bf0, st, kk + 1, std::true_type{}, 0, std::false_type{});
+                else kstep(af0, bf0, af1, bf1, st, kk + 1, std::true_type{}, 0, std::false_type{});
+            }
+            if constexpr (LOADS) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * NL));
+            else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __syncthreads();
-            if constexpr (LOADS) issue_loads(kt & 1);
-            if constexpr (NEXT) load_frags(nx, 0, af0, bf0);
-            mfma_step(af1, bf1);
-            interleave_hint<TM * TN, NEXT ? NDS : 0, LOADS ? NA + NB : 0>();
-            __builtin_amdgcn_sched_barrier(0);
+            kstep(af1, bf1, af0, bf0, nx, 0, next_c, sidx, loads_c);
         };
         {
             int kt = 0;
-            for (; kt + 2 < g.ktiles; ++kt) ktile(kt, std::true_type{}, std::true_type{});
-            if (g.ktiles >= 2) ktile(g.ktiles - 2, std::false_type{}, std::true_type{});
-            ktile(g.ktiles - 1, std::false_type{}, std::false_type{});
+            for (; kt + NS < g.ktiles; ++kt) ktile(kt, std::true_type{}, std::true_type{});
+            for (; kt + 1 < g.ktiles; ++kt) ktile(kt, std::false_type{}, std::true_type{});
+            ktile(kt, std::false_type{}, std::false_type{});
         }
 
         p_q = q;

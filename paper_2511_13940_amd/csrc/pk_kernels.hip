@@ -197,26 +197,48 @@ static pk_status make_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, 
     return PK_OK;
 }
 
-template <int BM, int BN, bool FP8, int EPI>
-static pk_status launch_gemm(const GemmArgs& a, int grid, hipStream_t stream) {
+static int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
+// Persistent launch: one workgroup per CU (a multiple of 8 so that workgroup id mod 8 stays the XCD), or fewer
+// when there are fewer tile slots.
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
+static pk_status launch_gemm(GemmArgs a, int slots, hipStream_t stream) {
     static bool configured = false;
-    auto kern = gemm_kernel<BM, BN, FP8, EPI>;
-    constexpr int lds = gemm_lds_bytes<BM, BN>();
+    auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI>;
+    constexpr int lds = gemm_lds_bytes<BM, BN, KB, NS>();
+    a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
     if (!configured) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return PK_ERR_HIP;
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, stream, a);
+    int grid = num_cus() / 8 * 8;
+    if (grid < 8) grid = 8;
+    if (slots < grid) grid = slots;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, stream, a);
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }
 
 template <int EPI>
-static pk_status dispatch_gemm(const GemmArgs& a, int grid, const TileCfg& tc, bool fp8, hipStream_t stream) {
+static pk_status dispatch_gemm(const GemmArgs& a, int slots, const TileCfg& tc, bool fp8, hipStream_t stream) {
     if (tc.bm == 256) {
-        return fp8 ? launch_gemm<256, 256, true, EPI>(a, grid, stream) : launch_gemm<256, 256, false, EPI>(a, grid, stream);
+        // bf16: 8 waves, 64-byte k-tiles in a ring of 4 LDS stages; fp8: 128-byte k-tiles, 2 stages
+        return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI>(a, slots, stream)
+                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, stream);
     }
-    return fp8 ? launch_gemm<128, 128, true, EPI>(a, grid, stream) : launch_gemm<128, 128, false, EPI>(a, grid, stream);
+    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, stream)
+               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, stream);
 }
 
 static uint64_t timeout_ticks(uint64_t timeout_us) {
