@@ -68,6 +68,20 @@ __device__ __forceinline__ void dma_load16(const char* sbase, uint32_t voff, uin
                  : "m0");
 }
 
+// 16-byte store that writes through to memory (system-coherent cache policy, streaming).  Together with an
+// explicit wait for the stores to complete (s_waitcnt vmcnt(0)) this is the "release" half of a signal without
+// the L2 write-back of a release fence: nothing dirty is left behind in the XCD's L2.  Inline assembly because
+// the cache-policy bits are not reachable from a plain store.
+__device__ __forceinline__ void store16_writethrough(void* p, i32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+}
+
+// Publish a flag whose data was written with store16_writethrough and has completed (every wave waited on its
+// stores and passed a workgroup barrier): a relaxed device-scope store is then enough.
+__device__ __forceinline__ void flag_publish(uint32_t* flag, uint32_t epoch) {
+    __hip_atomic_store(flag, epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 __device__ __forceinline__ void acquire_agent() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 __device__ __forceinline__ void release_agent() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 

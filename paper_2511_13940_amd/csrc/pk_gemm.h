@@ -197,7 +197,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             if (tid == 0) {
                 uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
                                                   : g.flags_out + (int64_t)p_q * g.flags_per_slot;
-                flag_signal(flags + (int64_t)p_tmi * g.tiles_n + p_tc, g.epoch);
+                flag_publish(flags + (int64_t)p_tmi * g.tiles_n + p_tc, g.epoch);
             }
         }
     };
@@ -369,8 +369,12 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                         const int row = p_row0 + wm * (BM / WM) + ti * 32 + half * ROWS_PASS + rs;
                         const int col = col_w0 + ch * (16 / OUT_ELEM);
                         if (row < p_row_end && col < g.n)
-                            __builtin_nontemporal_store(val, (i32x4*)(dst_base + (int64_t)(row - dst_row0) * dst_pitch +
-                                                                      (int64_t)col * OUT_ELEM));
+{
+                            char* dp = dst_base + (int64_t)(row - dst_row0) * dst_pitch + (int64_t)col * OUT_ELEM;
+                            // reduce-scatter tiles are consumed by another kernel through a flag: write through
+                            if constexpr (EPI == EPI_RS) store16_writethrough(dp, val);
+                            else __builtin_nontemporal_store(val, (i32x4*)dp);
+                        }
                     }
                 }
             }
@@ -452,10 +456,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         p_col0 = col0;
     }
 
-    // the last tile's stores: release at device scope in every wave, then publish its flag
+    // the last tile's stores: every wave waits for its write-through stores, then the flag is published
     if constexpr (EPI == EPI_RS) {
         if (p_q >= 0) {
-            release_agent();
+            __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
             __syncthreads();
             signal_prev();
         }
