@@ -25,6 +25,11 @@ struct ReduceArgs {
     uint64_t timeout_ticks;
 };
 
+// cache policy of the partial-slot loads: system-coherent (sc0 sc1) and streaming (nt).  The slots are written
+// by other workgroups / kernels (write-through) and announced through flags; loading them past this XCD's L2
+// makes an acquire fence (a whole-L2 invalidate per workgroup) unnecessary.
+constexpr int kCoherentStream = 1 | 2 | 16;
+
 template <int PT>   // PT > 0: compile-time P; PT == 0: runtime P
 __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     const int tid = threadIdx.x;
@@ -42,8 +47,10 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
         }
     }
     if (__syncthreads_or(late)) return;
-    acquire_agent();
 
+    const uint32_t slot_bytes = (uint32_t)(r.slot_elems * 4);
+    __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc((void*)r.partials, 0, (int)(slot_bytes * (uint32_t)P),
+                                                                   0x00020000);
     const int row_start = tmi * r.tile_m + sb * r.rows_sub;
     const int row_stop = min(min(row_start + r.rows_sub, (tmi + 1) * r.tile_m), r.rows);
     const int col0 = tc * r.tile_n;
@@ -52,14 +59,14 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     for (int idx = tid; idx < total; idx += 256) {
         const int rr = idx / cpr, cc = idx - rr * cpr;
         const int64_t off = (int64_t)(row_start + rr) * r.n + col0 + cc * 8;
-        const float* src = r.partials + off;
-        f32x4 v0[PT > 0 ? PT : 1], v1[PT > 0 ? PT : 1];
+        const uint32_t boff = (uint32_t)(off * 4);
         f32x4 s0, s1;
         if constexpr (PT > 0) {
+            f32x4 v0[PT], v1[PT];
 #pragma unroll
             for (int p = 0; p < PT; ++p) {
-                v0[p] = __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems));
-                v1[p] = __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems + 4));
+                v0[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream));
+                v1[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff + 16, p * slot_bytes, kCoherentStream));
             }
             s0 = v0[0];
             s1 = v1[0];
@@ -69,11 +76,11 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
                 s1 += v1[p];
             }
         } else {
-            s0 = __builtin_nontemporal_load((const f32x4*)src);
-            s1 = __builtin_nontemporal_load((const f32x4*)(src + 4));
+            s0 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff, 0, kCoherentStream));
+            s1 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff + 16, 0, kCoherentStream));
             for (int p = 1; p < P; ++p) {
-                s0 += __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems));
-                s1 += __builtin_nontemporal_load((const f32x4*)(src + (int64_t)p * r.slot_elems + 4));
+                s0 += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream));
+                s1 += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff + 16, p * slot_bytes, kCoherentStream));
             }
         }
         bf16x8 o = {(__bf16)s0[0], (__bf16)s0[1], (__bf16)s0[2], (__bf16)s0[3],
@@ -172,8 +179,9 @@ static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt,
     const int kt = dt == PK_FP8_E4M3 ? 128 : 64, nv = dt == PK_FP8_E4M3 ? 16 : 8;
     if (k % kt || n % nv) return PK_ERR_SHAPE;
     if (m > (1 << 30) || n > (1 << 30) || k > (1 << 30)) return PK_ERR_SHAPE;
-    // the kernels address each operand with 32-bit byte offsets from its base
+    // the kernels address each operand, and the fp32 partial slots, with 32-bit byte offsets from their base
     if (m * k * 2 >= ((int64_t)1 << 32) || k * n * 2 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
+    if (rs && m * n * 4 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
     *lm = m;
     *ln = n;
     *lk = k;
@@ -343,8 +351,8 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         r.tile_m = pl.tile_m;
         r.tile_n = pl.tile_n;
         r.tiles_n = pl.tiles_n;
-        r.sub = pl.tile_m / 32;
-        r.rows_sub = 32;
+        r.rows_sub = 8;                       // 8 rows x tile_n columns x P slots per workgroup
+        r.sub = pl.tile_m / r.rows_sub;
         r.slot_elems = rows * pl.local_n;
         r.flags_per_slot = pl.flags_per_slot;
         r.epoch = epoch;
