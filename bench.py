@@ -89,6 +89,11 @@ def main():
         if ev:
             ev[3].record(stream)
 
+    # a plain copy of known size (64 MiB read + 64 MiB written): the yardstick for HBM-traffic counters
+    cal_src = torch.ones(16 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+
     epoch = 0
     for _ in range(args.warmup):
         epoch += 1

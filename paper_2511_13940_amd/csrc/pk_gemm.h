@@ -48,6 +48,7 @@ struct GemmArgs {
     int32_t n_groups;
     int32_t group0;
     int32_t wg_per_group;     // 8 * ceil(grp_tile_rows * tiles_n / 8): tile slots of one group
+    int32_t band;             // tile rows swept column-major inside a group (1 = plain row-major)
     int32_t rank;
     // reduce-scatter epilogue
     float* partials;          // [P][rows_per_shard][n]
@@ -91,7 +92,6 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     constexpr int NA = A_BYTES / 1024 / NW, NB = B_BYTES / 1024 / NW;   // wave-wide loads per wave per k-tile
     constexpr int NL = NA + NB;
     constexpr int KS = FP8 ? KB / 64 : KB / 32;          // MFMA k-steps per k-tile
-    constexpr int BAND = 4;                              // tile rows swept column-major inside a group
     constexpr int EPI_OFF = NS * STAGE;                  // LDS offset of the epilogue staging area
     static_assert(KB == 64 || KB == 128, "k-tile is 64 or 128 bytes of A row");
     static_assert(KS >= 2 && KS % 2 == 0, "the fragment double buffer needs an even number of k-steps");
@@ -223,6 +223,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         const char* b_base = g.B;
         const int64_t b_step = (int64_t)B_ROWS * g.ldb;
         if (have) {
+            const int BAND = g.band;
             const int band = t / (BAND * g.tiles_n);
             const int rem = t - band * BAND * g.tiles_n;
             const int rows_in_band = min(BAND, g.grp_tile_rows - band * BAND);

@@ -167,6 +167,16 @@ static TileCfg pick_tile(int P, int64_t rows_per_shard, int64_t n) {
     return {128, 128};
 }
 
+// Shape of an XCD's run of tiles inside a scheduling group.  The run (`run` consecutive tiles in the group's
+// linear order) should be a compact block so that the tiles an XCD works on at the same time share A and B
+// panels in its L2: up to 32 tiles are resident per XCD, ideally 4 rows x 8 columns.  When a run is no longer
+// than a tile row (all-gather: one chunk's tiles are split 8 ways), plain row-major keeps each XCD on one A
+// panel and on the same B column strip in every chunk.
+static int pick_band(int grp_tile_rows, int tiles_n, int run) {
+    if (run <= tiles_n) return 1;
+    return grp_tile_rows < 4 ? grp_tile_rows : 4;
+}
+
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, bool rs,
@@ -325,6 +335,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         a.group0 = 0;
         const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
         a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
+        a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);
         a.rank = rank;
         a.partials = partials;
         a.outgoing = outgoing;
@@ -401,6 +412,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
     a.group0 = rank;
     const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
     a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
+    a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);
     a.rank = rank;
     a.C = (uint16_t*)C_local;
     a.chunk_flags = chunk_flags;

@@ -30,7 +30,7 @@ def bits_of(t):
 
 def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
-                withhold=None, state=None):
+                withhold=None, lazy=False):
     """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
 
     deliver = "pre": peer slots and their flags are in place before the call.
@@ -38,6 +38,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
                      in `order`, with `gap_us` between slots, launched before the op.
     withhold: a (q, tile) whose flag is never set (timeout tests; "pre" only).
     Returns dict with out_bits (uint16), outgoing, partials_after, flags_out, flags_in, status, plan.
+    lazy=True leaves the two big fp32 arrays on the device (keys outgoing_t, partials_t) instead.
     """
     plan = pk.pk_gemm_rs_plan(P, M, N, K, dtype)
     mp = M // P
@@ -72,13 +73,17 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
     pk.pk_gemm_rs(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
                   flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main)
     torch.cuda.synchronize()
-    return {"out_bits": bits_of(out), "outgoing": outgoing.cpu().numpy(), "partials_after": part.cpu().numpy(),
-            "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
-            "status": status.cpu().numpy(), "plan": plan}
+    res = {"out_bits": bits_of(out), "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
+           "status": status.cpu().numpy(), "plan": plan}
+    if lazy:
+        res["outgoing_t"], res["partials_t"] = outgoing, part
+    else:
+        res["outgoing"], res["partials_after"] = outgoing.cpu().numpy(), part.cpu().numpy()
+    return res
 
 
 def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None,
-                epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None):
+                epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None, fetch_A=True):
     """One pk_ag_gemm call.  chunks: list of P numpy bit arrays (M/P x K).
 
     deliver = "pre": every chunk is in A_gathered with its flag set before the call.
@@ -119,5 +124,5 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
     pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,
                   timeout_us, stream=main)
     torch.cuda.synchronize()
-    return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy(),
+    return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy() if fetch_A else None,
             "flags": flags.cpu().numpy()}
