@@ -124,12 +124,15 @@ def main():
     }
     dom = "gemm_kernel<256,256,bf16,RS> (cfg3)" if k_rs >= k_ag else "gemm_kernel<256,256,bf16,AG> (cfg4)"
     ach = kernels[dom]["TFLOP/s"]
+    traffic = measured_traffic()
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK_TFLOPS["bf16"],
-                "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS["bf16"], 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS["bf16"], 4), "traffic": traffic.get(dom),
+                "traffic_unit": "bytes beyond L2 per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
                 "kernel_ms": round(kernels[dom]["ms"], 4)}
     reduce_roofline = {"bound": "hbm", "kernel": "reduce_kernel<8> (cfg3)",
                        "achieved": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"], 1), "peak": PEAK_HBM_GBS,
                        "unit": "GB/s", "frac": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"] / PEAK_HBM_GBS, 4),
+                       "traffic": traffic.get("reduce_kernel<8> (cfg3)"), "algorithmic_bytes": red_bytes,
                        "kernel_ms": round(k_red, 4)}
 
     result = {
@@ -189,6 +192,22 @@ def main():
 
     result["setup_seconds"] = round(gen_s, 1)
     print(json.dumps(result))
+
+
+def measured_traffic():
+    """HBM-side traffic per launch of the step's kernels, as measured by the committed rocprofv3 counter runs
+    (bench.py cannot run the profiler on itself).  Returns {kernel label: bytes} or {} if the summary is absent."""
+    path = os.path.join(ROOT, "profiles", "bench_step_hbm_traffic.txt")
+    out = {}
+    try:
+        with open(path) as f:
+            for ln in f:
+                if ln.startswith("TRAFFIC|"):
+                    _, label, fetch, write = ln.strip().split("|")
+                    out[label] = int(fetch) + int(write)
+    except OSError:
+        pass
+    return out
 
 
 def extras(pk, wl, torch, np, L):
