@@ -242,18 +242,79 @@ def extras(pk, wl, torch, np, L):
     out["table3_style"] = {"gemm_ms": round(t_gemm, 4), "gemm_rs_ms": round(t_fused, 4),
                            "comm_ratio": round((t_fused - t_gemm) / t_fused, 4)}
 
-    # gather phase alone: the emulated communicator moving the 7 peer chunks (read + write)
+    # gather phase alone: the emulated communicator moving the 7 peer chunks (read + write), by workgroup count
     staging = L["A4"].clone()
     counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
     order = L["i4"]["order"]
-
-    def gather():
-        counters.zero_()
-        pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], L["chunk_flags"], 0x7FFFFFFF, order, 0, counters)
-    t_g = timeit(gather)
     moved = 2 * (c4.P - 1) * (c4.M // c4.P) * c4.K * 2
-    out["gather_phase"] = {"ms": round(t_g, 4), "GB/s": round(moved / (t_g * 1e-3) / 1e9, 1),
-                           "frac_of_hbm_peak": round(moved / (t_g * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    out["gather_phase"] = {}
+    for n_wg in (32, 256, 1024):
+        def gather():
+            counters.zero_()
+            pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], L["chunk_flags"], 0x7FFFFFFF, order, 0,
+                                     counters, n_wg=n_wg)
+        t_g = timeit(gather)
+        out["gather_phase"][f"{n_wg} workgroups"] = {"ms": round(t_g, 4), "GB/s": round(moved / (t_g * 1e-3) / 1e9, 1),
+                                                     "frac_of_hbm_peak": round(moved / (t_g * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+
+    # live all-gather: the chunks arrive in ring order through 32 communicator workgroups on a second stream while
+    # the GEMM runs on the other 224 compute units (inter-SM overlap); flags start below the epoch every iteration
+    side = torch.cuda.Stream()
+    flags_live = torch.zeros(c4.P, dtype=torch.int32, device="cuda")
+    done = torch.cuda.Event()
+    ep4 = [2 * 10 ** 6]
+
+    def ag_live():
+        ep4[0] += 1
+        done.record(stream)
+        side.wait_event(done)
+        with torch.cuda.stream(side):
+            counters.zero_()
+            pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_live, ep4[0], order, 0, counters,
+                                     stream=side, n_wg=32)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_live, ep4[0], L["C4"],
+                      L["status"], comm_cus=32)
+        stream.wait_stream(side)
+    t_live = timeit(ag_live)
+    t_pre224 = timeit(lambda: pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None,
+                                            L["chunk_flags"], 1, L["C4"], L["status"], comm_cus=32))
+    out["ag_gemm_live"] = {"ms_live_ring_arrival_32_comm_cus": round(t_live, 4), "ms_prelanded_224_cus": round(t_pre224, 4),
+                           "TFLOP/s_live": round(c4.flops / (t_live * 1e-3) / 1e12, 1)}
+
+    # cfg5: fp8 e4m3 GEMM+RS (HBM-bound: 2.28 GB of mandatory traffic for 1.1e12 flop)
+    c5 = wl.CONFIGS["cfg5"]
+    i5 = wl.gemm_rs_inputs(c5.P, c5.M, c5.N, c5.K, c5.dtype, rank, seed=0, order=c5.order)
+    p5 = pk.pk_gemm_rs_plan(c5.P, c5.M, c5.N, c5.K, c5.dtype)
+    mp5 = c5.M // c5.P
+    A5, B5 = torch.from_numpy(i5["A_local"]).cuda(), torch.from_numpy(i5["B_local"]).cuda()
+    sa5 = torch.tensor([float(i5["scale_a"])], dtype=torch.float32, device="cuda")
+    sb5 = torch.tensor([float(i5["scale_b"])], dtype=torch.float32, device="cuda")
+    part5 = torch.from_numpy(i5["partials"]).cuda()
+    outg5 = torch.zeros((c5.P, mp5, c5.N), dtype=torch.float32, device="cuda")
+    out5 = torch.zeros((mp5, c5.N), dtype=torch.int16, device="cuda")
+    fin5 = torch.full((c5.P, p5.flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    fin5[rank].zero_()
+    fout5 = torch.zeros_like(fin5)
+    ep5 = [0]
+
+    def rs5(phases):
+        def f():
+            if phases & 1:
+                ep5[0] += 1
+            pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part5, outg5, fin5, fout5, ep5[0], out5,
+                          phases, L["status"])
+        return f
+    t5 = timeit(rs5(pk.PHASE_ALL), n=5, w=2)
+    t5g = timeit(rs5(pk.PHASE_GEMM), n=5, w=2)
+    t5r = timeit(rs5(pk.PHASE_REDUCE), n=5, w=2)
+    bytes5 = 2 * c5.M * (c5.K // c5.P) + 2 * c5.M * c5.N * 4 + mp5 * c5.N * 2
+    red5 = c5.M * c5.N * 4 + mp5 * c5.N * 2
+    out["cfg5_fp8_gemm_rs"] = {"ms": round(t5, 4), "TFLOP/s": round(c5.flops / (t5 * 1e-3) / 1e12, 1),
+                               "GB/s_mandatory_traffic": round(bytes5 / (t5 * 1e-3) / 1e9, 1),
+                               "frac_of_hbm_peak": round(bytes5 / (t5 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                               "gemm_phase_ms": round(t5g, 4), "gemm_phase_TFLOP/s": round(c5.flops / (t5g * 1e-3) / 1e12, 1),
+                               "reduce_phase_ms": round(t5r, 4), "reduce_phase_GB/s": round(red5 / (t5r * 1e-3) / 1e9, 1)}
+    assert L["status"][0].item() == 0
     return out
 
 

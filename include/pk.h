@@ -119,6 +119,10 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  *   C_local     M x N/P bf16
  *
  * Output tiles are scheduled chunk by chunk starting from the own chunk, then rank+1, rank+2, ... (mod P).
+ * comm_cus (the paper's num_comm_sms, section 3.1.3 "SM partitioning", appendix D) is the number of compute
+ * units this call leaves free for the communicator workgroups that move the chunks while it runs: the GEMM is
+ * launched on the remaining ones (rounded down to a multiple of 8, at least 8).  0 = use every compute unit;
+ * then the communicator must already be resident when this kernel starts, or the chunks must have landed.
  * Requirements: M % P == 0, N % P == 0, K % 64 == 0 (bf16) or % 128 == 0 (fp8), (N/P) % 8 == 0 (bf16) or
  * % 16 == 0 (fp8).  With P == 1 this is a plain GEMM with bf16 output (chunk_flags may then be NULL).
  */
@@ -127,7 +131,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      const void* A_gathered, const void* B_local,
                      const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch,
-                     void* C_local,
+                     void* C_local, int comm_cus,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
@@ -142,6 +146,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  * flags_in[q][tile] = epoch after each tile; idle `gap_us` between slots.
  *
  * `order` is a HOST array of at most PK_EMU_MAX_ORDER distinct ranks (the caller excludes its own rank).
+ * n_wg is the number of communicator workgroups (one per compute unit; it sets the delivery bandwidth), 0 = 32.
  * `counters` is device scratch of at least PK_EMU_MAX_ORDER uint32, zeroed by the caller before each call.
  * Launch these on a second stream BEFORE the consuming call so that their workgroups are resident.
  */
@@ -149,12 +154,12 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
 pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes,
                                 const void* staging, void* A_gathered,
                                 uint32_t* chunk_flags, uint32_t epoch,
-                                const int* order /* host */, int n_order, uint32_t gap_us,
+                                const int* order /* host */, int n_order, uint32_t gap_us, int n_wg,
                                 uint32_t* counters, void* stream);
 pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n,
                                   const float* staging, float* partials,
                                   uint32_t* flags_in, uint32_t epoch,
-                                  const int* order /* host */, int n_order, uint32_t gap_us,
+                                  const int* order /* host */, int n_order, uint32_t gap_us, int n_wg,
                                   void* stream);
 
 #ifdef __cplusplus

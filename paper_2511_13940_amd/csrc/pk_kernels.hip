@@ -104,6 +104,8 @@ __device__ __forceinline__ void idle_us(uint32_t us) {
     while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(16);
 }
 
+// Both emulators publish like the GEMM epilogue does: write-through stores, every wave waits for its own stores,
+// workgroup barrier, then a relaxed device-scope flag store (no L2 write-back fence per workgroup).
 __global__ __launch_bounds__(256) void emu_chunks_kernel(const char* staging, char* A_gathered, int64_t chunk_bytes,
                                                          uint32_t* chunk_flags, uint32_t epoch, EmuOrder ord,
                                                          uint32_t gap_us, uint32_t* counters) {
@@ -112,14 +114,23 @@ __global__ __launch_bounds__(256) void emu_chunks_kernel(const char* staging, ch
         const int q = ord.q[i];
         const i32x4* src = (const i32x4*)(staging + (int64_t)q * chunk_bytes);
         i32x4* dst = (i32x4*)(A_gathered + (int64_t)q * chunk_bytes);
-        for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < n16; idx += (int64_t)gridDim.x * 256)
-            dst[idx] = __builtin_nontemporal_load(src + idx);
-        release_agent();
+        // 8 independent 16-byte loads in flight per thread: few workgroups must still move a chunk quickly
+        const int64_t stride = (int64_t)gridDim.x * 256;
+        int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        for (; idx + 7 * stride < n16; idx += 8 * stride) {
+            i32x4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(src + idx + u * stride);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) store16_writethrough(dst + idx + u * stride, v[u]);
+        }
+        for (; idx < n16; idx += stride) store16_writethrough(dst + idx, __builtin_nontemporal_load(src + idx));
+        __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
         __syncthreads();
         if (threadIdx.x == 0) {
             // the last workgroup to finish its part of the chunk publishes the flag
-            uint32_t old = __hip_atomic_fetch_add(counters + i, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-            if (old == gridDim.x - 1) flag_signal(chunk_flags + q, epoch);
+            uint32_t old = __hip_atomic_fetch_add(counters + i, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (old == gridDim.x - 1) flag_publish(chunk_flags + q, epoch);
         }
         idle_us(gap_us);
     }
@@ -141,11 +152,11 @@ __global__ __launch_bounds__(256) void emu_partials_kernel(const float* staging,
             for (int idx = threadIdx.x; idx < total; idx += 256) {
                 const int rr = idx / w4, cc = idx - rr * w4;
                 const int64_t off = (int64_t)q * slot_elems + (int64_t)(r0 + rr) * n + c0 + cc * 4;
-                *(f32x4*)(partials + off) = __builtin_nontemporal_load((const f32x4*)(staging + off));
+                store16_writethrough(partials + off, __builtin_nontemporal_load((const i32x4*)(staging + off)));
             }
-            release_agent();
+            __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
             __syncthreads();
-            if (threadIdx.x == 0) flag_signal(flags_in + (int64_t)q * fps + tile, epoch);
+            if (threadIdx.x == 0) flag_publish(flags_in + (int64_t)q * fps + tile, epoch);
         }
         idle_us(gap_us);
     }
@@ -231,7 +242,7 @@ static int num_cus() {
 // Persistent launch: one workgroup per CU (a multiple of 8 so that workgroup id mod 8 stays the XCD), or fewer
 // when there are fewer tile slots.
 template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
-static pk_status launch_gemm(GemmArgs a, int slots, hipStream_t stream) {
+static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, hipStream_t stream) {
     static bool configured = false;
     auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI>;
     constexpr int lds = gemm_lds_bytes<BM, BN, KB, NS>();
@@ -241,22 +252,26 @@ static pk_status launch_gemm(GemmArgs a, int slots, hipStream_t stream) {
             return PK_ERR_HIP;
         configured = true;
     }
-    int grid = num_cus() / 8 * 8;
+    int grid = (num_cus() - comm_cus) / 8 * 8;
     if (grid < 8) grid = 8;
-    if (slots < grid) grid = slots;
+    // the fewest workgroups that finish in the same number of rounds (448 slots on 256 CUs: 2 rounds of 224)
+    const int rounds = (slots + grid - 1) / grid;
+    const int even = ((slots + rounds - 1) / rounds + 7) / 8 * 8;
+    if (even < grid) grid = even;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, stream, a);
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }
 
 template <int EPI>
-static pk_status dispatch_gemm(const GemmArgs& a, int slots, const TileCfg& tc, bool fp8, hipStream_t stream) {
+static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const TileCfg& tc, bool fp8,
+                               hipStream_t stream) {
     if (tc.bm == 256) {
         // bf16: 8 waves, 64-byte k-tiles in a ring of 4 LDS stages; fp8: 128-byte k-tiles, 2 stages
-        return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI>(a, slots, stream)
-                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, stream);
+        return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI>(a, slots, comm_cus, stream)
+                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, stream);
     }
-    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, stream)
-               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, stream);
+    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, stream)
+               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, stream);
 }
 
 static uint64_t timeout_ticks(uint64_t timeout_us) {
@@ -348,7 +363,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         a.epoch = epoch;
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
-        st = dispatch_gemm<EPI_RS>(a, a.wg_per_group, tc, fp8, s);
+        st = dispatch_gemm<EPI_RS>(a, a.wg_per_group, 0, tc, fp8, s);
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
@@ -384,12 +399,13 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
 
 pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
-                     const uint32_t* chunk_flags, uint32_t epoch, void* C_local,
+                     const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus,
                      uint32_t* status, uint64_t timeout_us, void* stream) {
     pk_plan pl;
     pk_status st = make_plan(P, M, N, K, dt, false, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
+    if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
     const bool fp8 = dt == PK_FP8_E4M3;
     if (!A_gathered || !B_local || !C_local || !status) return PK_ERR_NULL;
     if (P > 1 && !chunk_flags) return PK_ERR_NULL;
@@ -421,7 +437,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
     a.epoch = epoch;
     a.status = status;
     a.timeout_ticks = timeout_ticks(timeout_us);
-    return dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, tc, fp8, (hipStream_t)stream);
+    return dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, (hipStream_t)stream);
 }
 
 static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
@@ -439,9 +455,10 @@ static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
 
 pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes, const void* staging, void* A_gathered,
                                 uint32_t* chunk_flags, uint32_t epoch, const int* order, int n_order,
-                                uint32_t gap_us, uint32_t* counters, void* stream) {
+                                uint32_t gap_us, int n_wg, uint32_t* counters, void* stream) {
     if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || K < 1 || M % P) return PK_ERR_SHAPE;
     if (elem_bytes != 1 && elem_bytes != 2) return PK_ERR_DTYPE;
+    if (n_wg < 0 || n_wg > 4096) return PK_ERR_ARG;
     if (!staging || !A_gathered || !chunk_flags || !counters) return PK_ERR_NULL;
     const int64_t chunk_bytes = (M / P) * K * elem_bytes;
     if (chunk_bytes % 16) return PK_ERR_SHAPE;
@@ -450,16 +467,16 @@ pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes, con
     pk_status st = make_order(order, n_order, P, &o);
     if (st != PK_OK) return st;
     if (n_order == 0) return PK_OK;
-    hipLaunchKernelGGL(emu_chunks_kernel, dim3(32), dim3(256), 0, (hipStream_t)stream, (const char*)staging,
+    hipLaunchKernelGGL(emu_chunks_kernel, dim3(n_wg ? n_wg : 32), dim3(256), 0, (hipStream_t)stream, (const char*)staging,
                        (char*)A_gathered, chunk_bytes, chunk_flags, epoch, o, gap_us, counters);
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }
 
 pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n, const float* staging,
                                   float* partials, uint32_t* flags_in, uint32_t epoch, const int* order, int n_order,
-                                  uint32_t gap_us, void* stream) {
+                                  uint32_t gap_us, int n_wg, void* stream) {
     if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || N < 1 || M % P || N % 4) return PK_ERR_SHAPE;
-    if (tile_m < 1 || tile_n < 4 || tile_n % 4) return PK_ERR_ARG;
+    if (tile_m < 1 || tile_n < 4 || tile_n % 4 || n_wg < 0 || n_wg > 4096) return PK_ERR_ARG;
     if (!staging || !partials || !flags_in) return PK_ERR_NULL;
     if (!aligned16(staging) || !aligned16(partials)) return PK_ERR_ALIGN;
     EmuOrder o;
@@ -468,7 +485,7 @@ pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int t
     if (n_order == 0) return PK_OK;
     const int rows = (int)(M / P);
     const int tiles_m = (int)ceil_div(rows, tile_m), tiles_n = (int)ceil_div(N, tile_n);
-    hipLaunchKernelGGL(emu_partials_kernel, dim3(32), dim3(256), 0, (hipStream_t)stream, staging, partials, flags_in,
+    hipLaunchKernelGGL(emu_partials_kernel, dim3(n_wg ? n_wg : 32), dim3(256), 0, (hipStream_t)stream, staging, partials, flags_in,
                        epoch, o, gap_us, rows, (int)N, tile_m, tile_n, tiles_m, tiles_n);
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }

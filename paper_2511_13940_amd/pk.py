@@ -57,11 +57,11 @@ def lib():
         L.pk_gemm_rs.restype = i32
         L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, u64, vp]
         L.pk_ag_gemm.restype = i32
-        L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, vp, u64, vp]
+        L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, vp, u64, vp]
         L.pk_emu_deliver_chunks.restype = i32
-        L.pk_emu_deliver_chunks.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, vp, vp]
+        L.pk_emu_deliver_chunks.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp, vp]
         L.pk_emu_deliver_partials.restype = i32
-        L.pk_emu_deliver_partials.argtypes = [i32, i64, i64, i32, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, vp]
+        L.pk_emu_deliver_partials.argtypes = [i32, i64, i64, i32, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp]
         _lib = L
     return _lib
 
@@ -119,10 +119,10 @@ def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, part
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
-               C_local, status, timeout_us=0, stream=None):
+               C_local, status, timeout_us=0, stream=None, comm_cus=0):
     _check(lib().pk_ag_gemm(P, rank, M, N, K, _dt(dtype), _ptr(A_gathered), _ptr(B_local), _ptr(scale_a),
-                            _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), _ptr(status), timeout_us,
-                            _stream(stream)), "pk_ag_gemm")
+                            _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus, _ptr(status),
+                            timeout_us, _stream(stream)), "pk_ag_gemm")
 
 
 def _order(order):
@@ -131,15 +131,15 @@ def _order(order):
 
 
 def pk_emu_deliver_chunks(P, M, K, elem_bytes, staging, A_gathered, chunk_flags, epoch, order, gap_us,
-                          counters, stream=None):
+                          counters, stream=None, n_wg=0):
     arr, n = _order(order)
     _check(lib().pk_emu_deliver_chunks(P, M, K, elem_bytes, _ptr(staging), _ptr(A_gathered), _ptr(chunk_flags),
-                                       epoch, arr, n, gap_us, _ptr(counters), _stream(stream)),
+                                       epoch, arr, n, gap_us, n_wg, _ptr(counters), _stream(stream)),
            "pk_emu_deliver_chunks")
 
 
 def pk_emu_deliver_partials(P, M, N, tile_m, tile_n, staging, partials, flags_in, epoch, order, gap_us,
-                            stream=None):
+                            stream=None, n_wg=0):
     arr, n = _order(order)
     _check(lib().pk_emu_deliver_partials(P, M, N, tile_m, tile_n, _ptr(staging), _ptr(partials), _ptr(flags_in),
-                                         epoch, arr, n, gap_us, _stream(stream)), "pk_emu_deliver_partials")
+                                         epoch, arr, n, gap_us, n_wg, _stream(stream)), "pk_emu_deliver_partials")

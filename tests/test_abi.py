@@ -87,8 +87,9 @@ def test_gemm_rs_argument_errors_launch_nothing():
 def test_ag_gemm_argument_errors_launch_nothing():
     f = pk.lib().pk_ag_gemm
 
-    def ag(P=4, rank=0, M=2048, N=4096, K=2048, dt=pk.BF16, A=0x1000, B=0x2000, flags=0x3000, C=0x4000, status=0x5000):
-        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, status, 0, None)
+    def ag(P=4, rank=0, M=2048, N=4096, K=2048, dt=pk.BF16, A=0x1000, B=0x2000, flags=0x3000, C=0x4000, status=0x5000,
+           comm=0):
+        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, comm, status, 0, None)
 
     assert ag(rank=4) == pk.ERR_RANK
     assert ag(N=4098) == pk.ERR_SHAPE        # N % P
@@ -98,21 +99,22 @@ def test_ag_gemm_argument_errors_launch_nothing():
     assert ag(flags=None) == pk.ERR_NULL
     assert ag(C=0x4002) == pk.ERR_ALIGN
     assert ag(dt=pk.FP8_E4M3) == pk.ERR_DTYPE
+    assert ag(comm=-1) == pk.ERR_ARG
 
 
 def test_emulator_argument_errors_launch_nothing():
     L = pk.lib()
     order = (ctypes.c_int * 3)(1, 2, 2)
-    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_ARG
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, 0x4000, None) == pk.ERR_ARG
     order = (ctypes.c_int * 3)(1, 2, 4)
-    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_ARG
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, 0x4000, None) == pk.ERR_ARG
     order = (ctypes.c_int * 3)(1, 2, 3)
-    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 4, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_DTYPE
-    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, None, 0x2000, 0x3000, 1, order, 3, 0, 0x4000, None) == pk.ERR_NULL
-    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0x4000, None) == pk.OK
-    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 65, 0, None) == pk.ERR_ARG
-    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 130, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, None) == pk.ERR_ARG
-    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, None) == pk.OK
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 4, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, 0x4000, None) == pk.ERR_DTYPE
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, None, 0x2000, 0x3000, 1, order, 3, 0, 0, 0x4000, None) == pk.ERR_NULL
+    assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0, 0x4000, None) == pk.OK
+    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 65, 0, 0, None) == pk.ERR_ARG
+    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 130, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, None) == pk.ERR_ARG
+    assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0, None) == pk.OK
 
 
 def test_binding_raises_pk_error():

@@ -81,9 +81,10 @@ def test_ag_gemm_full_size_sampled_rows(name, rank):
     c = wl.CONFIGS[name]
     inp = wl.ag_gemm_inputs(c.P, c.M, c.N, c.K, c.dtype, rank, seed=1, order=c.order)
     assert pk.pk_ag_gemm_plan(c.P, c.M, c.N, c.K, c.dtype).tile_m == 256
-    # ring-order arrival through the emulator while the GEMM runs, as in a live all-gather
+    # ring-order arrival through the emulator while the GEMM runs, as in a live all-gather: 32 compute units are
+    # left to the communicator workgroups, the GEMM runs on the other 224
     res = hz.run_ag_gemm(c.P, rank, c.M, c.N, c.K, c.dtype, inp["chunks"], inp["B_local"], epoch=4,
-                         deliver="emu", order=inp["order"], gap_us=5, fetch_A=False)
+                         deliver="emu", order=inp["order"], gap_us=5, fetch_A=False, comm_cus=32, n_wg=32)
     assert res["status"][0] == 0
     rows = sample_rows(c.M, c.P, 256, seed=rank)
     A = tp_gemm.gather_chunks(inp["chunks"])
