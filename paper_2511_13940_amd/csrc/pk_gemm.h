@@ -223,7 +223,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         const char* b_base = g.B;
         const int64_t b_step = (int64_t)B_ROWS * g.ldb;
         if (have) {
-            const int BAND = g.band;
+            const int BAND = g.band > 0 ? g.band : 1;
             const int band = t / (BAND * g.tiles_n);
             const int rem = t - band * BAND * g.tiles_n;
             const int rows_in_band = min(BAND, g.grp_tile_rows - band * BAND);
