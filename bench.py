@@ -241,6 +241,13 @@ def extras(pk, wl, torch, np, L):
     t_fused = timeit(fused)
     out["table3_style"] = {"gemm_ms": round(t_gemm, 4), "gemm_rs_ms": round(t_fused, 4),
                            "comm_ratio": round((t_fused - t_gemm) / t_fused, 4)}
+    # context only: the ROCm library GEMM (torch.matmul) on the same operands, i.e. the same data-dependent power draw
+    Ab, Bb = L["A3"].view(torch.bfloat16), L["B3"].view(torch.bfloat16)
+    Cl = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    t_lib = timeit(lambda: torch.matmul(Ab, Bb, out=Cl))
+    out["table3_style"]["library_gemm_ms"] = round(t_lib, 4)
+    out["table3_style"]["gemm_TFLOP/s"] = round(c3.flops / (t_gemm * 1e-3) / 1e12, 1)
+    out["table3_style"]["library_gemm_TFLOP/s"] = round(c3.flops / (t_lib * 1e-3) / 1e12, 1)
 
     # gather phase alone: the emulated communicator moving the 7 peer chunks (read + write), by workgroup count
     staging = L["A4"].clone()

@@ -8,8 +8,9 @@
 //     so that the loads of a k-tile have NS-1 k-tiles of time to land and are issued a few per k-tile;
 //   * A fragments are read with ds_read_b128, B fragments with the transposing ds_read_b64_tr_b16 /
 //     _tr_b8 (B is row-major K x N, the MFMA wants k-contiguous lanes);
-//   * both LDS tiles are XOR-swizzled at 16-byte-chunk granularity; a direct-to-LDS load writes lane l's
-//     16 bytes at base + 16*l, so the swizzle is applied by choosing which global chunk each lane fetches;
+//   * the A tile is XOR-swizzled at 16-byte-chunk granularity; the bf16 B tile is laid out as 64-column
+//     panels (the fp8 B tile as swizzled rows); a direct-to-LDS load writes lane l's 16 bytes at
+//     base + 16*l, so a layout is applied by choosing which global chunk each lane fetches;
 //   * the loop is software-pipelined: the fragments of k-step s+1 are read while the MFMAs of step s issue,
 //     and the single barrier of a k-tile sits before its last k-step, so the loads of a later k-tile and
 //     the first fragments of the next k-tile are issued under that step's MFMAs.
@@ -116,12 +117,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     const int s16 = l & 15, nhalf = (l >> 4) & 1;
     uint32_t b_off[TN];
     if constexpr (!FP8) {
+        // bf16 B tile: panels of 64 columns (128 bytes per k-row, k-rows consecutive);
+        // inside a row the two 32-byte pieces of each 64-byte half trade places on k-rows with bit 1 set
+        static_assert((BN / WN) % 64 == 0, "a wave column covers whole 64-column panels");
         const int krow_base = 8 * h + (s16 >> 2);
-        const int gsw = ((s16 >> 2) | (h << 2)) % (CPR / 4);
 #pragma unroll
         for (int tj = 0; tj < TN; ++tj) {
-            const int c = wn * (BN / WN / 8) + tj * 4 + 2 * nhalf + ((s16 & 3) >> 1);
-            b_off[tj] = (uint32_t)(A_BYTES + krow_base * B_ROW_BYTES + (c ^ (4 * gsw)) * 16 + (s16 & 1) * 8);
+            const int panel = wn * (BN / WN / 64) + (tj >> 1);
+            const int piece = (2 * (tj & 1) + nhalf) ^ ((s16 >> 3) & 1);
+            b_off[tj] = (uint32_t)(A_BYTES + panel * (B_ROWS * 128) + krow_base * 128 + piece * 32 + (s16 & 3) * 8);
         }
     } else {
         const int krow_base = 32 * h + (s16 >> 1);
@@ -141,9 +145,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             if (u < TN) {
                 const int tj = u;
                 s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk) * B_ROW_BYTES));
+                    (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk) * 128));
                 s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk + 4) * B_ROW_BYTES));
+                    (PK_LDS s16x4*)(st + b_off[tj] + (16 * kk + 4) * 128));
                 s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 bfr[tj] = __builtin_bit_cast(bf16x8, both);
             } else {
@@ -269,15 +273,27 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                     a_voff[j] = (uint32_t)((int64_t)grow * g.lda + (cp ^ fA(r)) * 16);
                 }
             }
-            {
+            if constexpr (!FP8) {
+                // 1 KB block bi of the B tile = 8 k-rows of one 64-column panel
+                const int kr_in = l >> 3, cp = l & 7;
+                const int n_bytes = g.n * 2;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int bi = j * NW + w;
+                    const int panel = bi / (B_ROWS / 8);
+                    const int kr = (bi % (B_ROWS / 8)) * 8 + kr_in;
+                    int colbyte = (col0 + panel * 64) * 2 + (cp ^ (2 * ((kr >> 1) & 1))) * 16;
+                    if (colbyte >= n_bytes) colbyte = n_bytes - 16;   // edge tile: valid memory, never stored
+                    b_voff[j] = (uint32_t)((int64_t)kr * g.ldb + colbyte);
+                }
+            } else {
                 const int kr_in = l / CPR, cp = l % CPR;
-                const int n_bytes = g.n * ELEM;
+                const int n_bytes = g.n;
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     const int kr = (j * NW + w) * RPI + kr_in;
-                    const int sw = FP8 ? 2 * ((kr & 7) % (CPR / 2))
-                                       : 4 * (((kr & 3) | ((kr >> 1) & 4)) % (CPR / 4));
-                    int colbyte = col0 * ELEM + (cp ^ sw) * 16;
+                    const int sw = 2 * ((kr & 7) % (CPR / 2));
+                    int colbyte = col0 + (cp ^ sw) * 16;
                     if (colbyte >= n_bytes) colbyte = n_bytes - 16;   // edge tile: valid memory, never stored
                     b_voff[j] = (uint32_t)((int64_t)kr * g.ldb + colbyte);
                 }
