@@ -109,9 +109,24 @@ def main():
     assert status[0].item() == 0, f"device status {status.tolist()}"
 
     ms_step = wall * 1e3 / args.steps
-    k_ag = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    k_rs = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-    k_red = sum(e[2].elapsed_time(e[3]) for e in evs) / args.steps
+    per = [[e[i].elapsed_time(e[i + 1]) for e in evs] for i in range(3)]
+    k_ag, k_rs, k_red = (sum(x) / args.steps for x in per)
+
+    # the MFMA rate this chip sustains in a register-only loop: operands all 1.0, then random sign + mantissa
+    # (data-dependent power lowers the clock); per-run context for the roofline fraction below
+    report = torch.zeros(4, dtype=torch.int64, device="cuda")
+    sustained = {}
+    for label, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        pk.pk_probe_mfma(2000, rnd, report)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        fl = pk.pk_probe_mfma(20000, rnd, report)
+        b.record(stream)
+        torch.cuda.synchronize()
+        rep = report.tolist()
+        sustained[label] = {"TFLOP/s": round(fl / (a.elapsed_time(b) * 1e-3) / 1e12, 1),
+                            "core_clock_MHz": round(100.0 * rep[1] / max(rep[0], 1))}
     flops = c3.flops + c4.flops
     value = flops / (ms_step * 1e-3) / 1e12
 
@@ -128,7 +143,9 @@ def main():
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK_TFLOPS["bf16"],
                 "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS["bf16"], 4), "traffic": traffic.get(dom),
                 "traffic_unit": "bytes beyond L2 per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
-                "kernel_ms": round(kernels[dom]["ms"], 4)}
+                "kernel_ms": round(kernels[dom]["ms"], 4),
+                "mfma_loop_sustained": sustained,
+                "frac_of_sustained_random": round(ach / sustained["random_operands"]["TFLOP/s"], 4)}
     reduce_roofline = {"bound": "hbm", "kernel": "reduce_kernel<8> (cfg3)",
                        "achieved": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"], 1), "peak": PEAK_HBM_GBS,
                        "unit": "GB/s", "frac": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"] / PEAK_HBM_GBS, 4),
@@ -147,6 +164,8 @@ def main():
         "roofline": roofline,
         "reduce_roofline": reduce_roofline,
         "kernels": {k: {kk: round(vv, 4) for kk, vv in v.items()} for k, v in kernels.items()},
+        "kernel_ms_median_min": {k: [round(sorted(x)[len(x) // 2], 4), round(min(x), 4)]
+                                 for k, x in zip(kernels, per)},
         "frac_of_mfma_peak_whole_step": round(value / PEAK_TFLOPS["bf16"], 4),
     }
 
@@ -216,15 +235,16 @@ def extras(pk, wl, torch, np, L):
     stream = L["stream"]
     out = {}
 
-    def timeit(fn, n=10, w=3):
+    def timeit(fn, n=10, w=3, st=None):
+        st = st or stream
         for _ in range(w):
             fn()
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(stream)
+        a.record(st)
         for _ in range(n):
             fn()
-        b.record(stream)
+        b.record(st)
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
@@ -264,29 +284,81 @@ def extras(pk, wl, torch, np, L):
         out["gather_phase"][f"{n_wg} workgroups"] = {"ms": round(t_g, 4), "GB/s": round(moved / (t_g * 1e-3) / 1e9, 1),
                                                      "frac_of_hbm_peak": round(moved / (t_g * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
 
-    # live all-gather: the chunks arrive in ring order through 32 communicator workgroups on a second stream while
-    # the GEMM runs on the other 224 compute units (inter-SM overlap); flags start below the epoch every iteration
-    side = torch.cuda.Stream()
-    flags_live = torch.zeros(c4.P, dtype=torch.int32, device="cuda")
-    done = torch.cuda.Event()
-    ep4 = [2 * 10 ** 6]
+    def live(COMM):
+        # live runs on a compute-unit partition (the paper's SM split): COMM compute units (COMM/8 per XCD) run the
+        # emulated communicator on one stream, the op runs on the others through a second stream; flags start below the
+        # epoch every iteration.  Feeder: 8 workgroups per communicator compute unit.
+        h_comp, h_comm = pk.pk_partition_create(COMM)
+        comp, side = torch.cuda.ExternalStream(h_comp), torch.cuda.ExternalStream(h_comm)
+        flags_live = torch.zeros(c4.P, dtype=torch.int32, device="cuda")
+        done = torch.cuda.Event()
+        ep4 = [2 * 10 ** 6]
+        torch.cuda.synchronize()
 
-    def ag_live():
-        ep4[0] += 1
-        done.record(stream)
-        side.wait_event(done)
-        with torch.cuda.stream(side):
-            counters.zero_()
+        def ag_live():
+            ep4[0] += 1
+            done.record(comp)
+            side.wait_event(done)
+            with torch.cuda.stream(side):
+                counters.zero_()
             pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_live, ep4[0], order, 0, counters,
-                                     stream=side, n_wg=32)
-        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_live, ep4[0], L["C4"],
-                      L["status"], comm_cus=32)
-        stream.wait_stream(side)
-    t_live = timeit(ag_live)
-    t_pre224 = timeit(lambda: pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None,
-                                            L["chunk_flags"], 1, L["C4"], L["status"], comm_cus=32))
-    out["ag_gemm_live"] = {"ms_live_ring_arrival_32_comm_cus": round(t_live, 4), "ms_prelanded_224_cus": round(t_pre224, 4),
-                           "TFLOP/s_live": round(c4.flops / (t_live * 1e-3) / 1e12, 1)}
+                                     stream=side, n_wg=8 * COMM)
+            pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_live, ep4[0], L["C4"],
+                          L["status"], comm_cus=COMM, stream=comp)
+            comp.wait_stream(side)
+        t_live = timeit(ag_live, st=comp)
+        t_pre224 = timeit(lambda: pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None,
+                                                L["chunk_flags"], 1, L["C4"], L["status"], comm_cus=COMM, stream=comp), st=comp)
+
+        def feeder_alone():
+            with torch.cuda.stream(side):
+                counters.zero_()
+            pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_live, 1, order, 0, counters,
+                                     stream=side, n_wg=8 * COMM)
+        t_feed = timeit(feeder_alone, st=side)
+        res = {}
+        res["ag_gemm_live"] = {"ms_live_ring_arrival": round(t_live, 4), "ms_prelanded_224_cus": round(t_pre224, 4),
+                               "ms_feeder_alone": round(t_feed, 4), "comm_cus": COMM,
+                               "TFLOP/s_live": round(c4.flops / (t_live * 1e-3) / 1e12, 1)}
+
+        # live reduce-scatter: the 7 peer slots arrive tile by tile through the emulated communicator
+        flags_live3 = torch.zeros_like(L["flags_in"])
+        stage3 = L["part"].clone()
+        p3 = L["p3"]
+        peers = [q for q in range(c3.P) if q != rank]
+        ep3 = [3 * 10 ** 6]
+        torch.cuda.synchronize()
+
+        def rs_live():
+            ep3[0] += 1
+            done.record(comp)
+            side.wait_event(done)
+            pk.pk_emu_deliver_partials(c3.P, c3.M, c3.N, p3.tile_m, p3.tile_n, stage3, L["part"], flags_live3, ep3[0],
+                                       peers, 0, stream=side, n_wg=8 * COMM)
+            pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                          flags_live3, L["flags_out"], ep3[0], L["out3"], pk.PHASE_ALL, L["status"], comm_cus=COMM, stream=comp)
+            comp.wait_stream(side)
+        t_rs_live = timeit(rs_live, st=comp)
+        ep3b = [4 * 10 ** 6]
+
+        def rs_pre224():
+            ep3b[0] += 1
+            pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                          L["flags_in"], L["flags_out"], ep3b[0], L["out3"], pk.PHASE_ALL, L["status"], comm_cus=COMM, stream=comp)
+        t_rs_pre224 = timeit(rs_pre224, st=comp)
+        res["gemm_rs_live"] = {"ms_live_peer_partials": round(t_rs_live, 4), "ms_prelanded_224_cus": round(t_rs_pre224, 4),
+                               "ms_prelanded_256_cus": out["table3_style"]["gemm_rs_ms"], "comm_cus": COMM}
+        torch.cuda.synchronize()
+        pk.pk_partition_destroy(h_comp, h_comm)
+        return res
+
+    out.update(live(32))
+    out["comm_cus_sweep"] = {}
+    for cc in (16, 64):
+        r = live(cc)
+        out["comm_cus_sweep"][str(cc)] = {"ag_gemm_live_ms": r["ag_gemm_live"]["ms_live_ring_arrival"],
+                                          "ag_feeder_alone_ms": r["ag_gemm_live"]["ms_feeder_alone"],
+                                          "gemm_rs_live_ms": r["gemm_rs_live"]["ms_live_peer_partials"]}
 
     # cfg5: fp8 e4m3 GEMM+RS (HBM-bound: 2.28 GB of mandatory traffic for 1.1e12 flop)
     c5 = wl.CONFIGS["cfg5"]

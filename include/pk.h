@@ -94,7 +94,8 @@ const char* pk_status_str(int status);
  *
  * Requirements: M % P == 0, K % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), N % 8 == 0 (bf16) or
  * % 16 == 0 (fp8); M/P and N need not be multiples of the tile (edge tiles are partial).  Otherwise
- * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).
+ * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).  comm_cus: as for pk_ag_gemm below, the
+ * number of compute units the GEMM phase leaves to communicator workgroups (0 = none).
  */
 pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
 pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
@@ -102,7 +103,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      const float* scale_a, const float* scale_b,
                      float* partials, float* outgoing,
                      uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases,
+                     void* out_shard, uint32_t phases, int comm_cus,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
@@ -161,6 +162,29 @@ pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int t
                                   uint32_t* flags_in, uint32_t epoch,
                                   const int* order /* host */, int n_order, uint32_t gap_us, int n_wg,
                                   void* stream);
+
+/*
+ * Measurement aid, not part of the method: a register-only loop of 32x32x16 bf16 MFMAs (2 workgroups of 4 waves
+ * per compute unit, `iters` rounds of 16 MFMAs per wave) on operands that are all 1.0 (random_operands = 0) or
+ * random sign + mantissa (1).  Timed by the caller with events around the call, it gives the MFMA rate the chip
+ * sustains at the clock it holds under that data; `*flops_out` (host, may be NULL) receives the flop count of the
+ * launch.  `report` is device memory of 4 uint64: [0] wall-clock ticks (100 MHz) and [1] core-clock cycles that one
+ * workgroup ran, [2..3] reserved.  Asynchronous on `stream`; PK_ERR_NULL / PK_ERR_ARG (iters outside [1, 2^22]).
+ */
+pk_status pk_probe_mfma(int iters, int random_operands, uint64_t* report, double* flops_out /* host */, void* stream);
+
+/*
+ * Compute-unit partition (paper section 3.1.3 "inter-SM overlapping" and its SM-partition study; appendix D
+ * num_comm_sms): creates two streams whose kernels run on disjoint sets of compute units, `comm_cus` of them
+ * (a multiple of 8 in [8, #CU - 8], spread evenly over the 8 XCDs) for the communicator side and the rest for
+ * the compute side.  Launch the communicator (here: pk_emu_deliver_*) on *comm_stream and pk_gemm_rs /
+ * pk_ag_gemm with the same comm_cus on *compute_stream: the persistent GEMM then fills exactly its partition and
+ * neither side waits for, or shares a compute unit with, the other.  Both handles are hipStream_t, owned by the
+ * caller until pk_partition_destroy (which does not synchronise: drain them first).  Host call; PK_ERR_NULL,
+ * PK_ERR_ARG (comm_cus), PK_ERR_HIP.
+ */
+pk_status pk_partition_create(int comm_cus, void** compute_stream /* host out */, void** comm_stream /* host out */);
+pk_status pk_partition_destroy(void* compute_stream, void* comm_stream);
 
 #ifdef __cplusplus
 }

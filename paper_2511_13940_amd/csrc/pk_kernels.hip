@@ -279,7 +279,53 @@ static uint64_t timeout_ticks(uint64_t timeout_us) {
     return timeout_us * kWallClockTicksPerUs;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Measurement aid (not part of the method): register-only MFMA loop.  Each wave runs `iters` rounds of 16
+// independent 32x32x16 bf16 MFMAs on operands held in registers, either all 1.0 or random sign + mantissa.
+// The sustained rate with random operands is the ceiling a GEMM on random data can reach: the chip lowers its
+// clock under data-dependent power.  One lane also reports wall-clock ticks and core-clock cycles.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_operands, uint64_t* report) {
+    const uint64_t w0 = wall_clock64(), c0 = clock64();
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    bf16x8 a[4], b[4];
+    uint32_t x = 1u + threadIdx.x * 2654435761u + blockIdx.x * 40503u;
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        s16x8 ra, rb;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            x = x * 1664525u + 1013904223u;
+            const uint32_t m1 = x >> 16;
+            x = x * 1664525u + 1013904223u;
+            const uint32_t m2 = x >> 16;
+            ra[j] = random_operands ? (short)((m1 & 0x807F) | 0x3C00) : (short)0x3F80;
+            rb[j] = random_operands ? (short)((m2 & 0x807F) | 0x3C00) : (short)0x3F80;
+        }
+        a[f] = __builtin_bit_cast(bf16x8, ra);
+        b[f] = __builtin_bit_cast(bf16x8, rb);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += acc[i][0];
+    if (threadIdx.x == 0 && blockIdx.x == 7) {
+        report[0] = wall_clock64() - w0;
+        report[1] = clock64() - c0;
+    }
+    if (sum == 12345.678f) report[2] = 1;   // keeps the loop alive
+}
+
 }  // namespace pk
+
 
 using namespace pk;
 
@@ -313,12 +359,14 @@ pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, p
 pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
                      float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases, uint32_t* status, uint64_t timeout_us, void* stream) {
+                     void* out_shard, uint32_t phases, int comm_cus, uint32_t* status, uint64_t timeout_us,
+                     void* stream) {
     pk_plan pl;
     pk_status st = make_plan(P, M, N, K, dt, true, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
     if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
+    if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
     const bool fp8 = dt == PK_FP8_E4M3;
     const bool do_gemm = phases & PK_PHASE_GEMM, do_reduce = phases & PK_PHASE_REDUCE;
     if (!partials || !flags_in || !status) return PK_ERR_NULL;
@@ -363,7 +411,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         a.epoch = epoch;
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
-        st = dispatch_gemm<EPI_RS>(a, a.wg_per_group, 0, tc, fp8, s);
+        st = dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, s);
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
@@ -488,6 +536,43 @@ pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int t
     hipLaunchKernelGGL(emu_partials_kernel, dim3(n_wg ? n_wg : 32), dim3(256), 0, (hipStream_t)stream, staging, partials, flags_in,
                        epoch, o, gap_us, rows, (int)N, tile_m, tile_n, tiles_m, tiles_n);
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
+}
+
+pk_status pk_probe_mfma(int iters, int random_operands, uint64_t* report, double* flops_out, void* stream) {
+    if (!report) return PK_ERR_NULL;
+    if (iters < 1 || iters > (1 << 22)) return PK_ERR_ARG;
+    const int n_wg = 2 * num_cus();
+    hipLaunchKernelGGL(probe_mfma_kernel, dim3(n_wg), dim3(256), 0, (hipStream_t)stream, iters, random_operands ? 1 : 0, report);
+    if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
+    if (flops_out) *flops_out = (double)n_wg * 4.0 * (double)iters * 16.0 * 32768.0;
+    return PK_OK;
+}
+
+pk_status pk_partition_create(int comm_cus, void** compute_stream, void** comm_stream) {
+    if (!compute_stream || !comm_stream) return PK_ERR_NULL;
+    const int ncu = num_cus();
+    if (comm_cus < 8 || comm_cus % 8 || comm_cus > ncu - 8 || ncu > 1024) return PK_ERR_ARG;
+    // Bit i of the mask is compute unit i/8 of XCD i%8 (checked on the device: a mask of the first 8*k bits
+    // enables k compute units on each of the 8 XCDs), so both partitions span all XCDs and their L2s.
+    uint32_t comm[32] = {0}, comp[32] = {0};
+    const int words = (ncu + 31) / 32;
+    for (int i = 0; i < ncu; ++i) (i < comm_cus ? comm : comp)[i >> 5] |= 1u << (i & 31);
+    hipStream_t sc = nullptr, sm = nullptr;
+    if (hipExtStreamCreateWithCUMask(&sc, words, comp) != hipSuccess) return PK_ERR_HIP;
+    if (hipExtStreamCreateWithCUMask(&sm, words, comm) != hipSuccess) {
+        (void)hipStreamDestroy(sc);
+        return PK_ERR_HIP;
+    }
+    *compute_stream = sc;
+    *comm_stream = sm;
+    return PK_OK;
+}
+
+pk_status pk_partition_destroy(void* compute_stream, void* comm_stream) {
+    pk_status st = PK_OK;
+    if (compute_stream && hipStreamDestroy((hipStream_t)compute_stream) != hipSuccess) st = PK_ERR_HIP;
+    if (comm_stream && hipStreamDestroy((hipStream_t)comm_stream) != hipSuccess) st = PK_ERR_HIP;
+    return st;
 }
 
 }  // extern "C"

@@ -20,7 +20,7 @@ EMU_MAX_ORDER = 64
 DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
 
 EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_ag_gemm_plan", "pk_ag_gemm",
-           "pk_emu_deliver_chunks", "pk_emu_deliver_partials"]
+           "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy"]
 
 
 class Plan(ctypes.Structure):
@@ -55,13 +55,19 @@ def lib():
             f.restype = i32
             f.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.pk_gemm_rs.restype = i32
-        L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, vp, u64, vp]
+        L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, vp, u64, vp]
         L.pk_ag_gemm.restype = i32
         L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, vp, u64, vp]
         L.pk_emu_deliver_chunks.restype = i32
         L.pk_emu_deliver_chunks.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp, vp]
         L.pk_emu_deliver_partials.restype = i32
         L.pk_emu_deliver_partials.argtypes = [i32, i64, i64, i32, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp]
+        L.pk_probe_mfma.restype = i32
+        L.pk_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pk_partition_create.restype = i32
+        L.pk_partition_create.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+        L.pk_partition_destroy.restype = i32
+        L.pk_partition_destroy.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -112,10 +118,10 @@ def pk_ag_gemm_plan(P, M, N, K, dtype):
 
 
 def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing,
-               flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None):
+               flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None, comm_cus=0):
     _check(lib().pk_gemm_rs(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
-                            _ptr(out_shard), phases, _ptr(status), timeout_us, _stream(stream)), "pk_gemm_rs")
+                            _ptr(out_shard), phases, comm_cus, _ptr(status), timeout_us, _stream(stream)), "pk_gemm_rs")
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
@@ -143,3 +149,22 @@ def pk_emu_deliver_partials(P, M, N, tile_m, tile_n, staging, partials, flags_in
     arr, n = _order(order)
     _check(lib().pk_emu_deliver_partials(P, M, N, tile_m, tile_n, _ptr(staging), _ptr(partials), _ptr(flags_in),
                                          epoch, arr, n, gap_us, n_wg, _stream(stream)), "pk_emu_deliver_partials")
+
+
+def pk_probe_mfma(iters, random_operands, report, stream=None):
+    """Launches the register-only MFMA loop; returns the flop count of the launch (time it with events)."""
+    flops = ctypes.c_double(0.0)
+    _check(lib().pk_probe_mfma(iters, 1 if random_operands else 0, _ptr(report), ctypes.byref(flops), _stream(stream)),
+           "pk_probe_mfma")
+    return flops.value
+
+
+def pk_partition_create(comm_cus):
+    """Two hipStream_t handles (ints) on disjoint compute units: (compute_stream, comm_stream)."""
+    a, b = ctypes.c_void_p(), ctypes.c_void_p()
+    _check(lib().pk_partition_create(comm_cus, ctypes.byref(a), ctypes.byref(b)), "pk_partition_create")
+    return a.value, b.value
+
+
+def pk_partition_destroy(compute_stream, comm_stream):
+    _check(lib().pk_partition_destroy(compute_stream, comm_stream), "pk_partition_destroy")

@@ -30,8 +30,11 @@ def bits_of(t):
 
 def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
-                withhold=None, lazy=False):
+                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0):
     """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
+
+    partition = (compute_stream, comm_stream) handles from pk_partition_create: the op then runs on the first and
+    the emulated peers on the second.
 
     deliver = "pre": peer slots and their flags are in place before the call.
     deliver = "emu": peer slots start as NaN; pk_emu_deliver_partials copies them in on a second stream,
@@ -54,7 +57,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
     peers = [q for q in range(P) if q != rank]
     if order is None:
         order = peers
-    main = torch.cuda.current_stream()
+    main = torch.cuda.current_stream() if partition is None else torch.cuda.ExternalStream(partition[0])
     if deliver == "pre":
         part = dev(partials.astype(np.float32))
         part[rank].fill_(NAN_POISON)
@@ -67,11 +70,12 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
         staging = dev(partials.astype(np.float32))
         part = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
         torch.cuda.synchronize()
-        side = torch.cuda.Stream()
+        side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
         pk.pk_emu_deliver_partials(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch,
-                                   list(order), gap_us, stream=side)
+                                   list(order), gap_us, stream=side, n_wg=n_wg)
     pk.pk_gemm_rs(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
-                  flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main)
+                  flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main,
+                  comm_cus=comm_cus)
     torch.cuda.synchronize()
     res = {"out_bits": bits_of(out), "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
            "status": status.cpu().numpy(), "plan": plan}
@@ -84,7 +88,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
 
 def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None, fetch_A=True,
-                comm_cus=0, n_wg=0):
+                comm_cus=0, n_wg=0, partition=None):
     """One pk_ag_gemm call.  chunks: list of P numpy bit arrays (M/P x K).
 
     deliver = "pre": every chunk is in A_gathered with its flag set before the call.
@@ -104,7 +108,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
     peers = [q for q in range(P) if q != rank]
     if order is None:
         order = [(rank + d) % P for d in range(1, P)]
-    main = torch.cuda.current_stream()
+    main = torch.cuda.current_stream() if partition is None else torch.cuda.ExternalStream(partition[0])
     full = np.concatenate([np.asarray(c, dtype=npdt) for c in chunks], axis=0)
     if deliver == "pre":
         A = elem_view(full, dtype)
@@ -120,7 +124,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
         A = elem_view(start, dtype)
         counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
         torch.cuda.synchronize()
-        side = torch.cuda.Stream()
+        side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
         pk.pk_emu_deliver_chunks(P, M, K, elem, staging, A, flags, epoch, list(order), gap_us, counters, stream=side,
                                  n_wg=n_wg)
     pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,

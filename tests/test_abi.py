@@ -63,7 +63,7 @@ def test_plan_errors(args, code):
 
 def _rs(P=2, rank=0, M=256, N=256, K=512, dt=pk.BF16, A=0x1000, B=0x2000, sa=None, sb=None, part=0x3000,
         outg=0x4000, fin=0x5000, fout=0x6000, out=0x7000, phases=3, status=0x8000):
-    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, status, 0, None)
+    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, 0, status, 0, None)
 
 
 def test_gemm_rs_argument_errors_launch_nothing():
@@ -82,6 +82,8 @@ def test_gemm_rs_argument_errors_launch_nothing():
     assert _rs(dt=pk.FP8_E4M3, K=256) == pk.ERR_DTYPE       # fp8 without scales
     assert _rs(M=255) == pk.ERR_SHAPE
     assert _rs(dt=5) == pk.ERR_DTYPE
+    assert pk.lib().pk_gemm_rs(2, 0, 256, 256, 512, pk.BF16, 0x1000, 0x2000, None, None, 0x3000, 0x4000, 0x5000, 0x6000, 1,
+                               0x7000, 3, -8, 0x8000, 0, None) == pk.ERR_ARG      # comm_cus
 
 
 def test_ag_gemm_argument_errors_launch_nothing():
@@ -115,6 +117,19 @@ def test_emulator_argument_errors_launch_nothing():
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 65, 0, 0, None) == pk.ERR_ARG
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 130, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, None) == pk.ERR_ARG
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0, None) == pk.OK
+
+
+def test_partition_and_probe_argument_errors_launch_nothing():
+    L = pk.lib()
+    a, b = ctypes.c_void_p(), ctypes.c_void_p()
+    assert L.pk_partition_create(32, None, ctypes.byref(b)) == pk.ERR_NULL
+    assert L.pk_partition_create(32, ctypes.byref(a), None) == pk.ERR_NULL
+    for bad in (0, 4, 12, -8, 1 << 20):
+        assert L.pk_partition_create(bad, ctypes.byref(a), ctypes.byref(b)) == pk.ERR_ARG
+    assert a.value is None and b.value is None
+    assert L.pk_partition_destroy(None, None) == pk.OK
+    assert L.pk_probe_mfma(100, 1, None, None, None) == pk.ERR_NULL
+    assert L.pk_probe_mfma(0, 1, 0x1000, None, None) == pk.ERR_ARG
 
 
 def test_binding_raises_pk_error():
