@@ -20,6 +20,14 @@ the column slice B[:, N_r] (K x N/P); after the gather it computes
     C[:, N_r] = A . B[:, N_r]                       (M x N/P).
 The order in which chunks arrive does not enter the definition.
 
+GEMM + all-reduce (section 3.1.3, inter-SM overlapping; section 4.1, figure
+"GEMM + AR").  Same operands as GEMM + reduce-scatter, but every rank ends with
+the whole reduced matrix, rounded to bf16:
+    full[i, j] = bf16( sum_{p<P} (A[:, K_p] . B[K_p, :])[i, j] )   (M x N).
+Rank r reduces the rows R_r (exactly the reduce-scatter result above), rounds
+them once and hands that rounded block to every rank; the rows R_q, q != r, of
+its own copy are the blocks the other ranks hand to it, taken as they come.
+
 Readings where the paper is silent (the 8-bit path is an extension):
   * the scattered output dimension is the row dimension M;
   * cross-rank sums are taken over float32 per-source partial slots (the
@@ -106,6 +114,33 @@ def gemm_rs_rows(P, rank, a_local_bits, b_local_bits, dtype, partials, rows,
             acc += own_rows[t] if p == rank else np.asarray(partials[p][i - rank * mp], dtype=np.float64)
         out_rows[t] = acc
     return own_rows, out_rows
+
+
+def gemm_ar(P, rank, a_local_bits, b_local_bits, dtype, partials, peer_rows,
+            scale_a=None, scale_b=None):
+    """One rank's GEMM + all-reduce.
+
+    partials:  as for gemm_rs.
+    peer_rows: [P][M/P][N] bf16 bit patterns (uint16); block q != rank is the
+               reduced, rounded row block R_q that rank q hands out.  Block
+               `rank` is ignored.
+    Returns a dict:
+      own, outgoing   as gemm_rs;
+      out             M/P x N float64, this rank's reduced rows, not rounded;
+      bcast_bf16      M/P x N uint16: `out` rounded once, what every rank receives;
+      full_bf16       M x N uint16: this rank's copy of the result (own rows
+                      rounded, the others as received).
+    """
+    rs = gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials, scale_a, scale_b)
+    mp, N = rs["out"].shape
+    peer_rows = np.asarray(peer_rows)
+    if peer_rows.shape != (P, mp, N) or peer_rows.dtype != np.uint16:
+        raise ValueError(f"peer_rows must be uint16 of shape {(P, mp, N)}")
+    full = np.empty((P, mp, N), dtype=np.uint16)
+    for q in range(P):
+        full[q] = rs["out_bf16"] if q == rank else peer_rows[q]
+    return {"own": rs["own"], "outgoing": rs["outgoing"], "out": rs["out"],
+            "bcast_bf16": rs["out_bf16"], "full_bf16": full.reshape(P * mp, N)}
 
 
 def reduce_partials(partials):

@@ -108,6 +108,61 @@ def test_gemm_rs_integer_brute_force_all_ranks(P, M, N, K):
         assert np.array_equal(codec.bf16_decode(res["out_bf16"]), full[r * mp:(r + 1) * mp])
 
 
+@pytest.mark.parametrize("P,M,N,K", [(2, 4, 3, 6), (4, 8, 2, 8)])
+def test_gemm_ar_integer_brute_force_all_ranks(P, M, N, K):
+    """GEMM + all-reduce on one global integer problem: rank r's reduced rows are rows R_r of the
+    unsharded product; handing every rank's rounded block to every other rank leaves each rank with
+    the same full product (here exactly representable in bf16)."""
+    A = wl.small_int_matrix((M, K), 33, 1)
+    B = wl.small_int_matrix((K, N), 33, 2)
+    full = np.array(_brute_int(A, B), dtype=np.float64)
+    kp, mp = K // P, M // P
+    local = [np.array(_brute_int(A[:, r * kp:(r + 1) * kp], B[r * kp:(r + 1) * kp, :]), dtype=np.float64)
+             for r in range(P)]
+    shares = [(_int_bits(A[:, r * kp:(r + 1) * kp], "bf16"), _int_bits(B[r * kp:(r + 1) * kp, :], "bf16"))
+              for r in range(P)]
+
+    def partials_for(r):
+        out = np.zeros((P, mp, N), dtype=np.float32)
+        for q in range(P):
+            if q != r:
+                out[q] = local[q][r * mp:(r + 1) * mp]
+        return out
+    nothing = np.full((P, mp, N), 0x7FC0, dtype=np.uint16)            # NaN blocks: first pass ignores none of them
+    first = [tp_gemm.gemm_ar(P, r, shares[r][0], shares[r][1], "bf16", partials_for(r), nothing) for r in range(P)]
+    for r in range(P):
+        assert np.array_equal(first[r]["out"], full[r * mp:(r + 1) * mp])
+        assert np.array_equal(codec.bf16_decode(first[r]["bcast_bf16"]), full[r * mp:(r + 1) * mp])
+        got = codec.bf16_decode(first[r]["full_bf16"])
+        assert np.array_equal(got[r * mp:(r + 1) * mp], full[r * mp:(r + 1) * mp])
+        others = np.delete(got.reshape(P, mp, N), r, axis=0)
+        assert np.isnan(others).all()                                  # received blocks pass through untouched
+    handed = np.stack([first[q]["bcast_bf16"] for q in range(P)])
+    for r in range(P):
+        handed_r = handed.copy()
+        handed_r[r] = 0x7FC0                                           # own block must come from the reduction
+        res = tp_gemm.gemm_ar(P, r, shares[r][0], shares[r][1], "bf16", partials_for(r), handed_r)
+        assert np.array_equal(codec.bf16_decode(res["full_bf16"]), full)
+
+
+def test_gemm_ar_rounds_own_rows_once_and_checks_shapes():
+    P, M, N, K = 2, 4, 8, 128
+    g = wl.global_problem(M, N, K, "bf16", seed=9)
+    a, b = wl.slice_gemm_rs(g, P, 1)
+    partials = np.zeros((P, M // P, N), dtype=np.float32)
+    partials[0] = 1.0 + 2.0 ** -9                                      # not a bf16 value
+    peer = np.zeros((P, M // P, N), dtype=np.uint16)
+    res = tp_gemm.gemm_ar(P, 1, a, b, "bf16", partials, peer)
+    rs = tp_gemm.gemm_rs(P, 1, a, b, "bf16", partials)
+    assert np.array_equal(res["bcast_bf16"], codec.bf16_encode(rs["out"]))
+    assert np.array_equal(res["full_bf16"][M // P:], res["bcast_bf16"])
+    assert np.array_equal(res["full_bf16"][:M // P], peer[0])
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_ar(P, 1, a, b, "bf16", partials, peer.astype(np.float32))
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_ar(P, 1, a, b, "bf16", partials, peer[:, :1])
+
+
 def test_linearity_and_shard_concatenation_random_bf16():
     """Sum over ranks of A[:,K_p].B[K_p,:] equals the unsharded GEMM (to float64 rounding),
     and the P reduced shards stacked give the whole product."""
