@@ -360,6 +360,30 @@ def extras(pk, wl, torch, np, L):
                                           "ag_feeder_alone_ms": r["ag_gemm_live"]["ms_feeder_alone"],
                                           "gemm_rs_live_ms": r["gemm_rs_live"]["ms_live_peer_partials"]}
 
+    # GEMM + all-reduce at the cfg3 shape (one rank's share: the reduce phase also hands the reduced rows to the 7 peers)
+    pa = pk.pk_gemm_ar_plan(c3.P, c3.M, c3.N, c3.K, c3.dtype)
+    mp3 = c3.M // c3.P
+    full = torch.zeros((c3.M, c3.N), dtype=torch.int16, device="cuda")
+    bcast = torch.zeros((c3.P, mp3, c3.N), dtype=torch.int16, device="cuda")
+    ar_in = torch.full((c3.P, pa.ar_flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    ar_in[rank].zero_()
+    ar_out = torch.zeros_like(ar_in)
+    epa = [5 * 10 ** 6]
+
+    def ar(phases):
+        def f():
+            if phases & 1:
+                epa[0] += 1
+            pk.pk_gemm_ar(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                          L["flags_in"], L["flags_out"], full, bcast, ar_in, ar_out, epa[0], phases, L["status"])
+        return f
+    t_ar = timeit(ar(pk.PHASE_ALL | pk.PHASE_WAIT))
+    t_ar_red = timeit(ar(pk.PHASE_REDUCE))
+    ar_red_bytes = c3.M * c3.N * 4 + c3.P * mp3 * c3.N * 2
+    out["gemm_ar_cfg3_shape"] = {"ms": round(t_ar, 4), "TFLOP/s": round(c3.flops / (t_ar * 1e-3) / 1e12, 1),
+                                 "reduce_and_hand_out_ms": round(t_ar_red, 4),
+                                 "reduce_and_hand_out_GB/s": round(ar_red_bytes / (t_ar_red * 1e-3) / 1e9, 1)}
+
     # cfg5: fp8 e4m3 GEMM+RS (HBM-bound: 2.28 GB of mandatory traffic for 1.1e12 flop)
     c5 = wl.CONFIGS["cfg5"]
     i5 = wl.gemm_rs_inputs(c5.P, c5.M, c5.N, c5.K, c5.dtype, rank, seed=0, order=c5.order)

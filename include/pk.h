@@ -57,6 +57,8 @@ typedef enum { PK_BF16 = 0, PK_FP8_E4M3 = 1 } pk_dtype;
 #define PK_PHASE_GEMM   1u   /* local GEMM + scatter of finished tiles + per-tile signal */
 #define PK_PHASE_REDUCE 2u   /* wait for the P partials of each own tile, sum, round, store */
 #define PK_PHASE_ALL    3u
+#define PK_PHASE_WAIT   4u   /* pk_gemm_ar only: wait until every rank's reduced rows have landed in out_full */
+#define PK_AR_ROWS      8    /* rows of out_full covered by one all-reduce ready flag (columns: tile_n) */
 
 /* Flag granularity and derived sizes for a problem; filled by the *_plan calls (host struct). */
 typedef struct {
@@ -64,6 +66,7 @@ typedef struct {
     int32_t tiles_m, tiles_n;     /* flag grid of one shard (GEMM+RS: M/P x N) or of C_local (AG+GEMM) */
     int64_t flags_per_slot;       /* tiles_m * tiles_n */
     int64_t local_m, local_n, local_k;   /* the per-rank GEMM */
+    int64_t ar_flags_per_slot;    /* pk_gemm_ar_plan only: ceil((M/P) / PK_AR_ROWS) * tiles_n, else 0 */
 } pk_plan;
 
 int pk_version(void);
@@ -104,6 +107,39 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      float* partials, float* outgoing,
                      uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
                      void* out_shard, uint32_t phases, int comm_cus,
+                     uint32_t* status, uint64_t timeout_us, void* stream);
+
+/*
+ * GEMM + all-reduce for rank `rank` (paper section 3.1.3, inter-SM overlapping: partial results are accumulated
+ * in HBM, completion is signalled per tile, and the reduction is done once by dedicated workers; section 4.1,
+ * figure "GEMM + AR").  Operands, `partials`, `outgoing`, `flags_in`, `flags_out` exactly as pk_gemm_rs.  There is
+ * no in-fabric reduction on an xGMI mesh, so the all-reduce is the reduce-scatter of pk_gemm_rs followed by handing
+ * the reduced, rounded rows R_rank to every rank:
+ *
+ *   out_full rows R_rank = bf16( sum_{p<P} partials[p] )        (written here, then ar_flags_in[rank][b] = epoch)
+ *   bcast_out[q]         = the same block, for q != rank         (then ar_flags_out[q][b] = epoch)
+ *   out_full rows R_q, q != rank: written by rank q (or pk_emu_deliver_partials on the array viewed as fp32 pairs),
+ *                          announced through ar_flags_in[q][b].
+ *
+ *   out_full      M x N bf16
+ *   bcast_out     [P][M/P][N] bf16; in a deployment slot q is rank q's out_full rows R_rank, peer-mapped.  Slot
+ *                 `rank` unused.  May be NULL when P == 1.
+ *   ar_flags_in   [P][ar_flags_per_slot], ar_flags_out likewise (NULL allowed when P == 1); flag b covers rows
+ *                 [PK_AR_ROWS * (b / tiles_n), +PK_AR_ROWS) x columns of tile b % tiles_n of one row block.
+ *
+ * phases: PK_PHASE_GEMM | PK_PHASE_REDUCE as pk_gemm_rs; PK_PHASE_WAIT adds a kernel that waits (bounded) until all
+ * of ar_flags_in has reached `epoch`, so that work queued behind this call on `stream` may read all of out_full.
+ * Shape requirements, comm_cus, status and timeout_us as pk_gemm_rs.
+ */
+pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
+pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_local, const void* B_local,
+                     const float* scale_a, const float* scale_b,
+                     float* partials, float* outgoing,
+                     uint32_t* flags_in, uint32_t* flags_out,
+                     void* out_full, void* bcast_out,
+                     uint32_t* ar_flags_in, uint32_t* ar_flags_out,
+                     uint32_t epoch, uint32_t phases, int comm_cus,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*

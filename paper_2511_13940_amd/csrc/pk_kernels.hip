@@ -23,6 +23,13 @@ struct ReduceArgs {
     uint32_t epoch;
     uint32_t* status;
     uint64_t timeout_ticks;
+    // all-reduce mode (bcast_out != nullptr or ar_flags_in != nullptr): the reduced block also goes to every
+    // other rank's slot of bcast_out, and each 8-row block is announced per destination
+    uint16_t* bcast_out;      // [P][rows][n] bf16
+    uint32_t* ar_flags_in;    // [P][ar_flags_per_slot]; only slot `rank` is written
+    uint32_t* ar_flags_out;   // [P][ar_flags_per_slot]
+    int64_t ar_flags_per_slot;
+    int32_t rank;
 };
 
 // cache policy of the partial-slot loads: system-coherent (sc0 sc1) and streaming (nt).  The slots are written
@@ -85,8 +92,33 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
         }
         bf16x8 o = {(__bf16)s0[0], (__bf16)s0[1], (__bf16)s0[2], (__bf16)s0[3],
                     (__bf16)s1[0], (__bf16)s1[1], (__bf16)s1[2], (__bf16)s1[3]};
-        __builtin_nontemporal_store(o, (bf16x8*)(r.out + off));
+        if (r.ar_flags_in) {
+            // all-reduce: consumers find these rows through flags, so write through
+            const i32x4 ov = __builtin_bit_cast(i32x4, o);
+            store16_writethrough(r.out + off, ov);
+            for (int q = 0; q < P; ++q)
+                if (q != r.rank) store16_writethrough(r.bcast_out + (int64_t)q * r.slot_elems + off, ov);
+        } else {
+            __builtin_nontemporal_store(o, (bf16x8*)(r.out + off));
+        }
     }
+    if (r.ar_flags_in && row_start < r.rows) {
+        // `signal` per destination for this 8-row block: every wave waits for its stores, then one lane per rank
+        __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
+        __syncthreads();
+        if (tid < P) {
+            const int64_t b = (int64_t)(row_start / PK_AR_ROWS) * r.tiles_n + tc;
+            uint32_t* f = (tid == r.rank ? r.ar_flags_in : r.ar_flags_out) + (int64_t)tid * r.ar_flags_per_slot + b;
+            flag_publish(f, r.epoch);
+        }
+    }
+}
+
+// Completion of the all-reduce on this rank: one thread per flag of ar_flags_in waits (bounded) for the epoch.
+__global__ __launch_bounds__(256) void ar_wait_kernel(const uint32_t* flags, int64_t n_flags, uint32_t epoch,
+                                                      uint32_t* status, uint64_t timeout_ticks) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n_flags && !flag_wait(flags + i, epoch, timeout_ticks)) report_timeout(status, (uint32_t)i, 3u);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -223,6 +255,7 @@ static pk_status make_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, 
     plan->local_m = m;
     plan->local_n = n;
     plan->local_k = k;
+    plan->ar_flags_per_slot = 0;
     return PK_OK;
 }
 
@@ -329,43 +362,23 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_o
 
 using namespace pk;
 
-extern "C" {
+struct AllReduceOut {
+    uint16_t* bcast_out;
+    uint32_t* ar_flags_in;
+    uint32_t* ar_flags_out;
+    int64_t ar_flags_per_slot;
+};
 
-int pk_version(void) { return 1; }
-
-const char* pk_status_str(int s) {
-    switch (s) {
-        case PK_OK: return "ok";
-        case PK_ERR_NULL: return "null pointer";
-        case PK_ERR_SHAPE: return "unsupported shape";
-        case PK_ERR_DTYPE: return "bad dtype or missing scales";
-        case PK_ERR_ALIGN: return "pointer not 16-byte aligned";
-        case PK_ERR_RANK: return "rank out of range";
-        case PK_ERR_ARG: return "invalid argument";
-        case PK_ERR_HIP: return "HIP launch failed";
-        case PK_ERR_TIMEOUT: return "timed out waiting for a ready flag";
-        default: return "unknown status";
-    }
-}
-
-pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
-    return make_plan(P, M, N, K, dt, true, plan);
-}
-
-pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
-    return make_plan(P, M, N, K, dt, false, plan);
-}
-
-pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
-                     const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
-                     float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases, int comm_cus, uint32_t* status, uint64_t timeout_us,
-                     void* stream) {
+// GEMM + reduce-scatter; with `ar` the reduce phase also hands the reduced rows to every rank (all-reduce)
+static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                              const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
+                              float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out,
+                              uint32_t epoch, void* out_shard, const AllReduceOut* ar, uint32_t phases, int comm_cus,
+                              uint32_t* status, uint64_t timeout_us, void* stream) {
     pk_plan pl;
     pk_status st = make_plan(P, M, N, K, dt, true, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
-    if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
     if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
     const bool fp8 = dt == PK_FP8_E4M3;
     const bool do_gemm = phases & PK_PHASE_GEMM, do_reduce = phases & PK_PHASE_REDUCE;
@@ -432,6 +445,13 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         r.epoch = epoch;
         r.status = status;
         r.timeout_ticks = timeout_ticks(timeout_us);
+        r.rank = rank;
+        if (ar) {
+            r.bcast_out = ar->bcast_out;
+            r.ar_flags_in = ar->ar_flags_in;
+            r.ar_flags_out = ar->ar_flags_out;
+            r.ar_flags_per_slot = ar->ar_flags_per_slot;
+        }
         const int grid = (int)(pl.flags_per_slot * r.sub);
         switch (P) {
             case 1: hipLaunchKernelGGL(reduce_kernel<1>, dim3(grid), dim3(256), 0, s, r); break;
@@ -440,6 +460,81 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
             case 8: hipLaunchKernelGGL(reduce_kernel<8>, dim3(grid), dim3(256), 0, s, r); break;
             default: hipLaunchKernelGGL(reduce_kernel<0>, dim3(grid), dim3(256), 0, s, r); break;
         }
+        if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
+    }
+    return PK_OK;
+}
+
+extern "C" {
+
+int pk_version(void) { return 1; }
+
+const char* pk_status_str(int s) {
+    switch (s) {
+        case PK_OK: return "ok";
+        case PK_ERR_NULL: return "null pointer";
+        case PK_ERR_SHAPE: return "unsupported shape";
+        case PK_ERR_DTYPE: return "bad dtype or missing scales";
+        case PK_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case PK_ERR_RANK: return "rank out of range";
+        case PK_ERR_ARG: return "invalid argument";
+        case PK_ERR_HIP: return "HIP launch failed";
+        case PK_ERR_TIMEOUT: return "timed out waiting for a ready flag";
+        default: return "unknown status";
+    }
+}
+
+pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    return make_plan(P, M, N, K, dt, true, plan);
+}
+
+pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    return make_plan(P, M, N, K, dt, false, plan);
+}
+
+pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
+                     float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
+                     void* out_shard, uint32_t phases, int comm_cus, uint32_t* status, uint64_t timeout_us,
+                     void* stream) {
+    if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
+    return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
+                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, status, timeout_us, stream);
+}
+
+pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    pk_status st = make_plan(P, M, N, K, dt, true, plan);
+    if (st != PK_OK) return st;
+    plan->ar_flags_per_slot = ceil_div(M / P, PK_AR_ROWS) * plan->tiles_n;
+    return PK_OK;
+}
+
+pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                     const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
+                     float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out,
+                     void* out_full, void* bcast_out, uint32_t* ar_flags_in, uint32_t* ar_flags_out,
+                     uint32_t epoch, uint32_t phases, int comm_cus, uint32_t* status, uint64_t timeout_us,
+                     void* stream) {
+    if (phases == 0 || (phases & ~(PK_PHASE_ALL | PK_PHASE_WAIT))) return PK_ERR_ARG;
+    if (!out_full || !ar_flags_in || !status) return PK_ERR_NULL;
+    if (P > 1 && (!bcast_out || !ar_flags_out)) return PK_ERR_NULL;
+    if (!aligned16(out_full) || !aligned16(bcast_out)) return PK_ERR_ALIGN;
+    pk_plan pl;
+    pk_status st = pk_gemm_ar_plan(P, M, N, K, dt, &pl);
+    if (st != PK_OK) return st;
+    if (rank < 0 || rank >= P) return PK_ERR_RANK;
+    AllReduceOut ar = {(uint16_t*)bcast_out, ar_flags_in, ar_flags_out, pl.ar_flags_per_slot};
+    if (phases & PK_PHASE_ALL) {
+        // the reduce phase writes rows R_rank of out_full
+        uint16_t* own_rows = (uint16_t*)out_full + (int64_t)rank * (M / P) * N;
+        st = gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
+                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, status, timeout_us, stream);
+        if (st != PK_OK) return st;
+    }
+    if (phases & PK_PHASE_WAIT) {
+        const int64_t n_flags = (int64_t)P * pl.ar_flags_per_slot;
+        hipLaunchKernelGGL(ar_wait_kernel, dim3((unsigned)ceil_div(n_flags, 256)), dim3(256), 0, (hipStream_t)stream,
+                           (const uint32_t*)ar_flags_in, n_flags, epoch, status, timeout_ticks(timeout_us));
         if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
     }
     return PK_OK;

@@ -15,19 +15,22 @@ LIB_PATH = os.path.join(_HERE, "libpk.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_RANK, ERR_ARG, ERR_HIP, ERR_TIMEOUT = range(9)
 BF16, FP8_E4M3 = 0, 1
-PHASE_GEMM, PHASE_REDUCE, PHASE_ALL = 1, 2, 3
+PHASE_GEMM, PHASE_REDUCE, PHASE_ALL, PHASE_WAIT = 1, 2, 3, 4
+AR_ROWS = 8
 EMU_MAX_ORDER = 64
 DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
 
 EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_ag_gemm_plan", "pk_ag_gemm",
-           "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy"]
+           "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy",
+           "pk_gemm_ar_plan", "pk_gemm_ar"]
 
 
 class Plan(ctypes.Structure):
     _fields_ = [("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32),
                 ("tiles_m", ctypes.c_int32), ("tiles_n", ctypes.c_int32),
                 ("flags_per_slot", ctypes.c_int64),
-                ("local_m", ctypes.c_int64), ("local_n", ctypes.c_int64), ("local_k", ctypes.c_int64)]
+                ("local_m", ctypes.c_int64), ("local_n", ctypes.c_int64), ("local_k", ctypes.c_int64),
+                ("ar_flags_per_slot", ctypes.c_int64)]
 
 
 class PkError(RuntimeError):
@@ -51,7 +54,7 @@ def lib():
         L.pk_version.restype = ctypes.c_int
         L.pk_status_str.restype = ctypes.c_char_p
         L.pk_status_str.argtypes = [i32]
-        for f in (L.pk_gemm_rs_plan, L.pk_ag_gemm_plan):
+        for f in (L.pk_gemm_rs_plan, L.pk_ag_gemm_plan, L.pk_gemm_ar_plan):
             f.restype = i32
             f.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.pk_gemm_rs.restype = i32
@@ -64,6 +67,9 @@ def lib():
         L.pk_emu_deliver_partials.argtypes = [i32, i64, i64, i32, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp]
         L.pk_probe_mfma.restype = i32
         L.pk_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pk_gemm_ar.restype = i32
+        L.pk_gemm_ar.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, i32,
+                                 vp, u64, vp]
         L.pk_partition_create.restype = i32
         L.pk_partition_create.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
         L.pk_partition_destroy.restype = i32
@@ -122,6 +128,21 @@ def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, part
     _check(lib().pk_gemm_rs(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
                             _ptr(out_shard), phases, comm_cus, _ptr(status), timeout_us, _stream(stream)), "pk_gemm_rs")
+
+
+def pk_gemm_ar_plan(P, M, N, K, dtype):
+    p = Plan()
+    _check(lib().pk_gemm_ar_plan(P, M, N, K, _dt(dtype), ctypes.byref(p)), "pk_gemm_ar_plan")
+    return p
+
+
+def pk_gemm_ar(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in, flags_out,
+               out_full, bcast_out, ar_flags_in, ar_flags_out, epoch, phases, status, timeout_us=0, stream=None,
+               comm_cus=0):
+    _check(lib().pk_gemm_ar(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
+                            _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), _ptr(out_full),
+                            _ptr(bcast_out), _ptr(ar_flags_in), _ptr(ar_flags_out), epoch, phases, comm_cus,
+                            _ptr(status), timeout_us, _stream(stream)), "pk_gemm_ar")
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,

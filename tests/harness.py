@@ -132,3 +132,64 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
     torch.cuda.synchronize()
     return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy() if fetch_A else None,
             "flags": flags.cpu().numpy()}
+
+
+def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, scale_a=None, scale_b=None, epoch=1,
+                deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL | pk.PHASE_WAIT,
+                withhold_rows=None):
+    """One pk_gemm_ar call.  partials as run_gemm_rs; peer_rows: numpy [P][M/P][N] uint16, block q != rank is what
+    rank q hands out for rows R_q of out_full.
+
+    deliver = "pre": peers' partial slots and row blocks are in place with their flags set.
+    deliver = "emu": both arrive through pk_emu_deliver_partials on a second stream (the bf16 rows as fp32 pairs),
+                     into NaN-poisoned memory, partial slots first.
+    withhold_rows: (q, flag index) of ar_flags_in never set ("pre" only).
+    """
+    plan = pk.pk_gemm_ar_plan(P, M, N, K, dtype)
+    mp, fps, afps = M // P, plan.flags_per_slot, plan.ar_flags_per_slot
+    A, B = elem_view(A_bits, dtype), elem_view(B_bits, dtype)
+    sa, sb = scale_t(scale_a), scale_t(scale_b)
+    poison_rows = np.full((P, mp, N), 0x7FC1, dtype=np.uint16)
+    outgoing = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+    bcast = dev(poison_rows.view(np.int16))
+    flags_in = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
+    flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
+    ar_in = torch.zeros((P, afps), dtype=torch.int32, device="cuda")
+    ar_out = torch.zeros((P, afps), dtype=torch.int32, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    peers = [q for q in range(P) if q != rank]
+    if order is None:
+        order = peers
+    main = torch.cuda.current_stream()
+    peer_rows = np.ascontiguousarray(peer_rows, dtype=np.uint16)
+    if deliver == "pre":
+        part = dev(partials.astype(np.float32))
+        part[rank].fill_(NAN_POISON)
+        start = peer_rows.copy()
+        start[rank] = 0x7FC1
+        full = dev(start.view(np.int16).reshape(M, N))
+        for q in peers:
+            flags_in[q].fill_(epoch)
+            ar_in[q].fill_(epoch)
+        if withhold_rows is not None:
+            ar_in[withhold_rows[0], withhold_rows[1]] = epoch - 1
+        torch.cuda.synchronize()
+    else:
+        staging = dev(partials.astype(np.float32))
+        staging_rows = dev(peer_rows.view(np.int16))
+        part = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+        full = dev(poison_rows.view(np.int16).reshape(M, N))
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        pk.pk_emu_deliver_partials(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us,
+                                   stream=side)
+        # the bf16 row blocks as fp32 pairs: N/2 columns, PK_AR_ROWS x tile_n/2 per flag
+        pk.pk_emu_deliver_partials(P, M, N // 2, pk.AR_ROWS, plan.tile_n // 2, staging_rows, full, ar_in, epoch,
+                                   list(order), gap_us, stream=side)
+    pk.pk_gemm_ar(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None, flags_in,
+                  flags_out if P > 1 else None, full, bcast if P > 1 else None, ar_in, ar_out if P > 1 else None, epoch,
+                  phases, status, timeout_us, stream=main)
+    torch.cuda.synchronize()
+    return {"full_bits": bits_of(full), "bcast_bits": bits_of(bcast), "ar_in": ar_in.cpu().numpy(),
+            "ar_out": ar_out.cpu().numpy(), "flags_out": flags_out.cpu().numpy(), "status": status.cpu().numpy(),
+            "outgoing": outgoing.cpu().numpy(), "plan": plan}

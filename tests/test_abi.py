@@ -119,6 +119,33 @@ def test_emulator_argument_errors_launch_nothing():
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0, None) == pk.OK
 
 
+def test_gemm_ar_plan_and_argument_errors_launch_nothing():
+    p = pk.pk_gemm_ar_plan(8, 8192, 8192, 28672, "bf16")
+    assert (p.tile_m, p.tile_n, p.flags_per_slot) == (256, 256, 4 * 32)
+    assert p.ar_flags_per_slot == (1024 // pk.AR_ROWS) * 32
+    assert pk.pk_gemm_rs_plan(8, 8192, 8192, 28672, "bf16").ar_flags_per_slot == 0
+    p = pk.pk_gemm_ar_plan(2, 2 * 100, 264, 256, "bf16")                  # ragged: 100 rows -> 13 row blocks
+    assert p.ar_flags_per_slot == 13 * p.tiles_n
+    f = pk.lib().pk_gemm_ar
+
+    def ar(P=2, rank=0, M=256, N=256, K=512, full=0x9000, bc=0xA000, ai=0xB000, ao=0xC000, phases=7, status=0x8000,
+           part=0x3000):
+        return f(P, rank, M, N, K, pk.BF16, 0x1000, 0x2000, None, None, part, 0x4000, 0x5000, 0x6000, full, bc, ai, ao,
+                 1, phases, 0, status, 0, None)
+
+    assert ar(phases=0) == pk.ERR_ARG
+    assert ar(phases=8) == pk.ERR_ARG
+    assert ar(full=None) == pk.ERR_NULL
+    assert ar(bc=None) == pk.ERR_NULL
+    assert ar(ai=None) == pk.ERR_NULL
+    assert ar(ao=None) == pk.ERR_NULL
+    assert ar(status=None) == pk.ERR_NULL
+    assert ar(full=0x9008) == pk.ERR_ALIGN
+    assert ar(rank=2) == pk.ERR_RANK
+    assert ar(M=255) == pk.ERR_SHAPE
+    assert ar(part=None) == pk.ERR_NULL
+
+
 def test_partition_and_probe_argument_errors_launch_nothing():
     L = pk.lib()
     a, b = ctypes.c_void_p(), ctypes.c_void_p()
