@@ -30,8 +30,9 @@ its own copy are the blocks the other ranks hand to it, taken as they come.
 
 Readings where the paper is silent (the 8-bit path is an extension):
   * the scattered output dimension is the row dimension M;
-  * cross-rank sums are taken over float32 per-source partial slots (the
-    oracle adds them in float64, slot order 0..P-1);
+  * cross-rank sums are taken over per-source partial slots, float32 by
+    default, bf16 as the paper's variant (the oracle adds them in float64, slot
+    order 0..P-1);
   * 8-bit inputs carry one float32 scale per tensor; the unscaled products are
     accumulated and the product of the two scales is applied once at the end.
 """
@@ -63,9 +64,28 @@ def local_product(a_bits, b_bits, dtype, scale_a=None, scale_b=None, rows=None):
     return _scale(scale_a, scale_b) * (a @ b)
 
 
+def _slot_values(partials, partial_dtype, shape):
+    """The partial slots as float64, from float32 values or bf16 bit patterns."""
+    partials = np.asarray(partials)
+    if partials.shape != shape:
+        raise ValueError(f"partials shape {partials.shape} != {shape}")
+    if partial_dtype == "f32":
+        return partials.astype(np.float64)
+    if partial_dtype == "bf16":
+        if partials.dtype != np.uint16:
+            raise ValueError("bf16 partial slots are passed as uint16 bit patterns")
+        return codec.bf16_decode(partials)
+    raise ValueError(f"unknown partial dtype {partial_dtype!r}")
+
+
 def gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials,
-            scale_a=None, scale_b=None):
+            scale_a=None, scale_b=None, partial_dtype="f32"):
     """One rank's GEMM + reduce-scatter.
+
+    partial_dtype "f32" (default): the slots hold float32 values.  "bf16": the
+    slots hold bf16 values (the paper's element size for communicated tiles,
+    section 3.1.3, s = 2), passed as uint16 bit patterns; every contribution,
+    this rank's own included, is rounded to bf16 once before the sum.
 
     a_local_bits: M x K/P, b_local_bits: K/P x N.
     partials:     [P][M/P][N] float32; slot q (q != rank) is what rank q sent for
@@ -82,19 +102,18 @@ def gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials,
     if M % P:
         raise ValueError("M must be a multiple of P")
     mp = M // P
-    partials = np.asarray(partials)
-    if partials.shape != (P, mp, N):
-        raise ValueError(f"partials shape {partials.shape} != {(P, mp, N)}")
+    slots = _slot_values(partials, partial_dtype, (P, mp, N))
     outgoing = own.reshape(P, mp, N)
+    mine = outgoing[rank] if partial_dtype == "f32" else codec.bf16_round(outgoing[rank])
     out = np.zeros((mp, N), dtype=np.float64)
     for p in range(P):
-        out += outgoing[rank] if p == rank else partials[p].astype(np.float64)
+        out += mine if p == rank else slots[p]
     return {"own": own, "outgoing": outgoing, "out": out,
             "out_bf16": codec.bf16_encode(out)}
 
 
 def gemm_rs_rows(P, rank, a_local_bits, b_local_bits, dtype, partials, rows,
-                 scale_a=None, scale_b=None):
+                 scale_a=None, scale_b=None, partial_dtype="f32"):
     """The same result restricted to the global rows `rows` of the local product.
 
     Returns (own_rows, out_rows): own_rows is len(rows) x N float64; out_rows has
@@ -111,13 +130,18 @@ def gemm_rs_rows(P, rank, a_local_bits, b_local_bits, dtype, partials, rows,
             continue
         acc = np.zeros(own_rows.shape[1], dtype=np.float64)
         for p in range(P):
-            acc += own_rows[t] if p == rank else np.asarray(partials[p][i - rank * mp], dtype=np.float64)
+            if p == rank:
+                acc += own_rows[t] if partial_dtype == "f32" else codec.bf16_round(own_rows[t])
+            elif partial_dtype == "f32":
+                acc += np.asarray(partials[p][i - rank * mp], dtype=np.float64)
+            else:
+                acc += codec.bf16_decode(np.asarray(partials[p][i - rank * mp], dtype=np.uint16))
         out_rows[t] = acc
     return own_rows, out_rows
 
 
 def gemm_ar(P, rank, a_local_bits, b_local_bits, dtype, partials, peer_rows,
-            scale_a=None, scale_b=None):
+            scale_a=None, scale_b=None, partial_dtype="f32"):
     """One rank's GEMM + all-reduce.
 
     partials:  as for gemm_rs.
@@ -131,7 +155,7 @@ def gemm_ar(P, rank, a_local_bits, b_local_bits, dtype, partials, peer_rows,
       full_bf16       M x N uint16: this rank's copy of the result (own rows
                       rounded, the others as received).
     """
-    rs = gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials, scale_a, scale_b)
+    rs = gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials, scale_a, scale_b, partial_dtype)
     mp, N = rs["out"].shape
     peer_rows = np.asarray(peer_rows)
     if peer_rows.shape != (P, mp, N) or peer_rows.dtype != np.uint16:

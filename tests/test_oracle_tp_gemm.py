@@ -163,6 +163,56 @@ def test_gemm_ar_rounds_own_rows_once_and_checks_shapes():
         tp_gemm.gemm_ar(P, 1, a, b, "bf16", partials, peer[:, :1])
 
 
+def test_bf16_partial_slots_round_every_contribution_once():
+    """s = 2 variant: the own contribution is rounded to bf16 before the sum, the peers' slots are bf16.
+    Hand-made case: own = 1 + 2^-8 (a tie, rounds to 1.0), peer slot = 2^-8.  bf16 slots: 1.0 + 2^-8 is again a
+    tie and ends at 0x3F80; fp32 slots keep own exact: 1 + 2^-7 = 0x3F81."""
+    a = codec.bf16_encode(np.array([[1.0, 2.0 ** -8]]))              # 1 x 2
+    b = codec.bf16_encode(np.array([[1.0], [1.0]]))                  # 2 x 1
+    P, rank = 1, 0
+    assert tp_gemm.local_product(a, b, "bf16")[0, 0] == 1.0 + 2.0 ** -8
+    # P = 2 with rank 0 owning row 0 (M = 2: second row of A is zero)
+    a2 = np.concatenate([a, np.zeros_like(a)], axis=0)
+    p32 = np.zeros((2, 1, 1), np.float32)
+    p32[1] = 2.0 ** -8
+    p16 = codec.bf16_encode(p32.astype(np.float64))
+    r32 = tp_gemm.gemm_rs(2, 0, a2, b, "bf16", p32)
+    r16 = tp_gemm.gemm_rs(2, 0, a2, b, "bf16", p16, partial_dtype="bf16")
+    assert r32["out"][0, 0] == 1.0 + 2.0 ** -7 and r32["out_bf16"][0, 0] == 0x3F81
+    assert r16["out"][0, 0] == 1.0 + 2.0 ** -8 and r16["out_bf16"][0, 0] == 0x3F80
+    rows32 = tp_gemm.gemm_rs_rows(2, 0, a2, b, "bf16", p32, [0, 1])[1]
+    rows16 = tp_gemm.gemm_rs_rows(2, 0, a2, b, "bf16", p16, [0, 1], partial_dtype="bf16")[1]
+    assert rows32[0, 0] == r32["out"][0, 0] and rows16[0, 0] == r16["out"][0, 0]
+    assert np.isnan(rows16[1]).all()
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_rs(2, 0, a2, b, "bf16", p32, partial_dtype="bf16")      # float32 array is not bit patterns
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_rs(2, 0, a2, b, "bf16", p32, partial_dtype="fp16")
+
+
+@pytest.mark.parametrize("P,M,N,K", [(2, 4, 3, 6), (4, 8, 2, 8)])
+def test_bf16_partial_slots_integer_problem_equals_fp32_slots(P, M, N, K):
+    """Small integers are exact in bf16, so both slot types give the rows of the unsharded product."""
+    A = wl.small_int_matrix((M, K), 41, 1)
+    B = wl.small_int_matrix((K, N), 41, 2)
+    full = np.array(_brute_int(A, B), dtype=np.float64)
+    kp, mp = K // P, M // P
+    local = [np.array(_brute_int(A[:, r * kp:(r + 1) * kp], B[r * kp:(r + 1) * kp, :]), dtype=np.float64)
+             for r in range(P)]
+    for r in range(P):
+        p32 = np.zeros((P, mp, N), dtype=np.float32)
+        for q in range(P):
+            if q != r:
+                p32[q] = local[q][r * mp:(r + 1) * mp]
+        p16 = codec.bf16_encode(p32.astype(np.float64))
+        a, b = _int_bits(A[:, r * kp:(r + 1) * kp], "bf16"), _int_bits(B[r * kp:(r + 1) * kp, :], "bf16")
+        res = tp_gemm.gemm_rs(P, r, a, b, "bf16", p16, partial_dtype="bf16")
+        assert np.array_equal(res["out"], full[r * mp:(r + 1) * mp])
+        peer = np.zeros((P, mp, N), np.uint16)
+        ar = tp_gemm.gemm_ar(P, r, a, b, "bf16", p16, peer, partial_dtype="bf16")
+        assert np.array_equal(codec.bf16_decode(ar["bcast_bf16"]), full[r * mp:(r + 1) * mp])
+
+
 def test_linearity_and_shard_concatenation_random_bf16():
     """Sum over ranks of A[:,K_p].B[K_p,:] equals the unsharded GEMM (to float64 rounding),
     and the P reduced shards stacked give the whole product."""
