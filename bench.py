@@ -417,6 +417,32 @@ def extras(pk, wl, torch, np, L):
                                "frac_of_hbm_peak": round(bytes5 / (t5 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                "gemm_phase_ms": round(t5g, 4), "gemm_phase_TFLOP/s": round(c5.flops / (t5g * 1e-3) / 1e12, 1),
                                "reduce_phase_ms": round(t5r, 4), "reduce_phase_GB/s": round(red5 / (t5r * 1e-3) / 1e9, 1)}
+    # the paper's own element size for communicated tiles (s = 2): bf16 partial slots halve scatter and reduce traffic
+    out["bf16_partial_slots"] = {}
+    for name, c, A, B, sa, sb, part32, fin, fout, o in (("cfg3", c3, L["A3"], L["B3"], None, None, L["part"], L["flags_in"],
+                                                         L["flags_out"], L["out3"]),
+                                                        ("cfg5", c5, A5, B5, sa5, sb5, part5, fin5, fout5, out5)):
+        ref_bits = o.clone()                                   # result of the fp32-slot runs above (same inputs)
+        part16 = part32.to(torch.bfloat16).view(torch.int16)
+        outg16 = torch.zeros(part16.shape, dtype=torch.int16, device="cuda")
+        ep = [6 * 10 ** 6]
+
+        def rs16(phases):
+            def f():
+                if phases & 1:
+                    ep[0] += 1
+                pk.pk_gemm_rs(c.P, rank, c.M, c.N, c.K, c.dtype, A, B, sa, sb, part16, outg16, fin, fout, ep[0], o, phases,
+                              L["status"], partial_dtype="bf16")
+            return f
+        t_all = timeit(rs16(pk.PHASE_ALL), n=10, w=3)
+        t_g = timeit(rs16(pk.PHASE_GEMM), n=10, w=3)
+        t_r = timeit(rs16(pk.PHASE_REDUCE), n=10, w=3)
+        got = o.view(torch.bfloat16).float()
+        ref = ref_bits.view(torch.bfloat16).float()
+        out["bf16_partial_slots"][name] = {
+            "ms": round(t_all, 4), "gemm_phase_ms": round(t_g, 4), "reduce_phase_ms": round(t_r, 4),
+            "TFLOP/s": round(c.flops / (t_all * 1e-3) / 1e12, 1),
+            "max_abs_diff_vs_fp32_slots_over_rms": round(((got - ref).abs().max() / ref.pow(2).mean().sqrt()).item(), 5)}
     assert L["status"][0].item() == 0
     return out
 

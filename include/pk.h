@@ -53,6 +53,14 @@ typedef enum {
 
 typedef enum { PK_BF16 = 0, PK_FP8_E4M3 = 1 } pk_dtype;
 
+/* element type of the partial slots of pk_gemm_rs / pk_gemm_ar (`partials`, `outgoing`) */
+typedef enum {
+    PK_PARTIAL_F32 = 0,    /* fp32 slots: the default, every contribution enters the sum unrounded */
+    PK_PARTIAL_BF16 = 1    /* bf16 slots (the paper's element size for communicated tiles, section 3.1.3: s = 2):
+                              half the scatter and reduce traffic; every contribution, the own one included, is
+                              rounded to bf16 once before the fp32 sum */
+} pk_partial_dtype;
+
 /* phases of pk_gemm_rs (bit mask) */
 #define PK_PHASE_GEMM   1u   /* local GEMM + scatter of finished tiles + per-tile signal */
 #define PK_PHASE_REDUCE 2u   /* wait for the P partials of each own tile, sum, round, store */
@@ -87,9 +95,9 @@ const char* pk_status_str(int status);
  *   A_local   M x K/P      bf16 (2 B) or e4m3 (1 B)
  *   B_local   K/P x N      same element type
  *   scale_a, scale_b       one fp32 each, fp8 only (NULL for bf16)
- *   partials  [P][M/P][N]  fp32.  Slot q != rank is written by peer q (or by pk_emu_deliver_partials);
- *                          slot `rank` is written by this call.
- *   outgoing  [P][M/P][N]  fp32.  Slot q != rank receives this rank's tiles for rank q; slot `rank` unused.
+ *   partials  [P][M/P][N]  fp32, or bf16 with partial_dt = PK_PARTIAL_BF16.  Slot q != rank is written by peer q
+ *                          (or by pk_emu_deliver_partials); slot `rank` is written by this call.
+ *   outgoing  [P][M/P][N]  same element type.  Slot q != rank receives this rank's tiles for rank q; slot `rank` unused.
  *                          May be NULL when P == 1.
  *   flags_in  [P][flags_per_slot] readiness of partials[q][tile]; slot `rank` is signalled by this call.
  *   flags_out [P][flags_per_slot] signalled by this call when outgoing[q][tile] is complete.
@@ -98,15 +106,16 @@ const char* pk_status_str(int status);
  * Requirements: M % P == 0, K % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), N % 8 == 0 (bf16) or
  * % 16 == 0 (fp8); M/P and N need not be multiples of the tile (edge tiles are partial).  Otherwise
  * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).  comm_cus: as for pk_ag_gemm below, the
- * number of compute units the GEMM phase leaves to communicator workgroups (0 = none).
+ * number of compute units the GEMM phase leaves to communicator workgroups (0 = none).  partial_dt: element type of
+ * `partials` and `outgoing` (PK_ERR_DTYPE if unknown).
  */
 pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
 pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local,
                      const float* scale_a, const float* scale_b,
-                     float* partials, float* outgoing,
+                     void* partials, void* outgoing,
                      uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases, int comm_cus,
+                     void* out_shard, uint32_t phases, int comm_cus, int partial_dt /* pk_partial_dtype */,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
@@ -129,17 +138,17 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  *
  * phases: PK_PHASE_GEMM | PK_PHASE_REDUCE as pk_gemm_rs; PK_PHASE_WAIT adds a kernel that waits (bounded) until all
  * of ar_flags_in has reached `epoch`, so that work queued behind this call on `stream` may read all of out_full.
- * Shape requirements, comm_cus, status and timeout_us as pk_gemm_rs.
+ * Shape requirements, comm_cus, partial_dt, status and timeout_us as pk_gemm_rs.
  */
 pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
 pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local,
                      const float* scale_a, const float* scale_b,
-                     float* partials, float* outgoing,
+                     void* partials, void* outgoing,
                      uint32_t* flags_in, uint32_t* flags_out,
                      void* out_full, void* bcast_out,
                      uint32_t* ar_flags_in, uint32_t* ar_flags_out,
-                     uint32_t epoch, uint32_t phases, int comm_cus,
+                     uint32_t epoch, uint32_t phases, int comm_cus, int partial_dt /* pk_partial_dtype */,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*

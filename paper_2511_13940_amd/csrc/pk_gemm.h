@@ -31,7 +31,7 @@
 
 namespace pk {
 
-enum { EPI_RS = 0, EPI_AG = 1 };
+enum { EPI_RS = 0, EPI_AG = 1, EPI_RS16 = 2 };   // reduce-scatter with fp32 slots, all-gather, reduce-scatter with bf16 slots
 
 struct GemmArgs {
     const char* A;            // local first operand, row-major
@@ -52,8 +52,8 @@ struct GemmArgs {
     int32_t band;             // tile rows swept column-major inside a group (1 = plain row-major)
     int32_t rank;
     // reduce-scatter epilogue
-    float* partials;          // [P][rows_per_shard][n]
-    float* outgoing;          // [P][rows_per_shard][n]
+    void* partials;           // [P][rows_per_shard][n], fp32 (EPI_RS) or bf16 (EPI_RS16)
+    void* outgoing;           // [P][rows_per_shard][n]
     uint32_t* flags_in;       // [P][flags_per_slot]
     uint32_t* flags_out;      // [P][flags_per_slot]
     int64_t slot_elems;       // rows_per_shard * n
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     if constexpr (FP8) scale = g.scale_a[0] * g.scale_b[0];
 
     auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
-        if constexpr (EPI == EPI_RS) {
+        if constexpr (EPI != EPI_AG) {
             if (tid == 0) {
                 uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
                                                   : g.flags_out + (int64_t)p_q * g.flags_per_slot;
@@ -340,11 +340,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             char* dst_base;
             int64_t dst_pitch;
             int dst_row0;                                    // global row -> row inside the destination
-            if constexpr (EPI == EPI_RS) {
-                float* d = (p_q == g.rank) ? g.partials + (int64_t)g.rank * g.slot_elems
-                                           : g.outgoing + (int64_t)p_q * g.slot_elems;
-                dst_base = (char*)d;
-                dst_pitch = (int64_t)g.n * 4;
+            if constexpr (EPI != EPI_AG) {
+                dst_base = (p_q == g.rank) ? (char*)g.partials + (int64_t)g.rank * g.slot_elems * OUT_ELEM
+                                           : (char*)g.outgoing + (int64_t)p_q * g.slot_elems * OUT_ELEM;
+                dst_pitch = (int64_t)g.n * OUT_ELEM;
                 dst_row0 = p_q * g.rows_per_shard;
             } else {
                 dst_base = (char*)g.C;
@@ -389,7 +388,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 {
                             char* dp = dst_base + (int64_t)(row - dst_row0) * dst_pitch + (int64_t)col * OUT_ELEM;
                             // reduce-scatter tiles are consumed by another kernel through a flag: write through
-                            if constexpr (EPI == EPI_RS) store16_writethrough(dp, val);
+                            if constexpr (EPI != EPI_AG) store16_writethrough(dp, val);
                             else __builtin_nontemporal_store(val, (i32x4*)dp);
                         }
                     }
@@ -474,7 +473,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     }
 
     // the last tile's stores: every wave waits for its write-through stores, then the flag is published
-    if constexpr (EPI == EPI_RS) {
+    if constexpr (EPI != EPI_AG) {
         if (p_q >= 0) {
             __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
             __syncthreads();

@@ -14,7 +14,7 @@ namespace pk {
 // One workgroup handles `rows_sub` rows of one flag tile after waiting for that tile's P flags.
 // ------------------------------------------------------------------------------------------------
 struct ReduceArgs {
-    const float* partials;    // [P][rows][n]
+    const void* partials;     // [P][rows][n] fp32, or bf16 when the kernel is instantiated with S16
     uint16_t* out;            // rows x n bf16
     const uint32_t* flags_in; // [P][flags_per_slot]
     int32_t P, rows, n;
@@ -37,7 +37,7 @@ struct ReduceArgs {
 // makes an acquire fence (a whole-L2 invalidate per workgroup) unnecessary.
 constexpr int kCoherentStream = 1 | 2 | 16;
 
-template <int PT>   // PT > 0: compile-time P; PT == 0: runtime P
+template <int PT, bool S16>   // PT > 0: compile-time P; PT == 0: runtime P.  S16: the slots hold bf16
 __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     const int tid = threadIdx.x;
     const int tile = blockIdx.x / r.sub;
@@ -55,7 +55,8 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     }
     if (__syncthreads_or(late)) return;
 
-    const uint32_t slot_bytes = (uint32_t)(r.slot_elems * 4);
+    constexpr int SLOT_ELEM = S16 ? 2 : 4;
+    const uint32_t slot_bytes = (uint32_t)(r.slot_elems * SLOT_ELEM);
     __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc((void*)r.partials, 0, (int)(slot_bytes * (uint32_t)P),
                                                                    0x00020000);
     const int row_start = tmi * r.tile_m + sb * r.rows_sub;
@@ -63,12 +64,39 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     const int col0 = tc * r.tile_n;
     const int cpr = min(r.tile_n, r.n - col0) >> 3;          // 8-element chunks per row of this tile
     const int total = (row_stop - row_start) * cpr;
+    // bf16 -> fp32 of the 8 values of one 16-byte load, added to (s0, s1)
+    auto add16 = [](f32x4& s0, f32x4& s1, i32x4 v) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t w = (uint32_t)v[e];
+            const float lo = __builtin_bit_cast(float, w << 16), hi = __builtin_bit_cast(float, w & 0xFFFF0000u);
+            if (e < 2) {
+                s0[2 * e] += lo;
+                s0[2 * e + 1] += hi;
+            } else {
+                s1[2 * e - 4] += lo;
+                s1[2 * e - 3] += hi;
+            }
+        }
+    };
     for (int idx = tid; idx < total; idx += 256) {
         const int rr = idx / cpr, cc = idx - rr * cpr;
         const int64_t off = (int64_t)(row_start + rr) * r.n + col0 + cc * 8;
-        const uint32_t boff = (uint32_t)(off * 4);
+        const uint32_t boff = (uint32_t)(off * SLOT_ELEM);
         f32x4 s0, s1;
-        if constexpr (PT > 0) {
+        if constexpr (S16) {
+            s0 = f32x4{0.f, 0.f, 0.f, 0.f};
+            s1 = s0;
+            if constexpr (PT > 0) {
+                i32x4 v[PT];
+#pragma unroll
+                for (int p = 0; p < PT; ++p) v[p] = __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream);
+#pragma unroll
+                for (int p = 0; p < PT; ++p) add16(s0, s1, v[p]);
+            } else {
+                for (int p = 0; p < P; ++p) add16(s0, s1, __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream));
+            }
+        } else if constexpr (PT > 0) {
             f32x4 v0[PT], v1[PT];
 #pragma unroll
             for (int p = 0; p < PT; ++p) {
@@ -372,14 +400,16 @@ struct AllReduceOut {
 // GEMM + reduce-scatter; with `ar` the reduce phase also hands the reduced rows to every rank (all-reduce)
 static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                               const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
-                              float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out,
+                              void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out,
                               uint32_t epoch, void* out_shard, const AllReduceOut* ar, uint32_t phases, int comm_cus,
-                              uint32_t* status, uint64_t timeout_us, void* stream) {
+                              int partial_dt, uint32_t* status, uint64_t timeout_us, void* stream) {
     pk_plan pl;
     pk_status st = make_plan(P, M, N, K, dt, true, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
     if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
+    if (partial_dt != PK_PARTIAL_F32 && partial_dt != PK_PARTIAL_BF16) return PK_ERR_DTYPE;
+    const bool bf16_slots = partial_dt == PK_PARTIAL_BF16;
     const bool fp8 = dt == PK_FP8_E4M3;
     const bool do_gemm = phases & PK_PHASE_GEMM, do_reduce = phases & PK_PHASE_REDUCE;
     if (!partials || !flags_in || !status) return PK_ERR_NULL;
@@ -424,7 +454,8 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.epoch = epoch;
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
-        st = dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, s);
+        st = bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, s)
+                        : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, s);
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
@@ -453,13 +484,18 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
             r.ar_flags_per_slot = ar->ar_flags_per_slot;
         }
         const int grid = (int)(pl.flags_per_slot * r.sub);
-        switch (P) {
-            case 1: hipLaunchKernelGGL(reduce_kernel<1>, dim3(grid), dim3(256), 0, s, r); break;
-            case 2: hipLaunchKernelGGL(reduce_kernel<2>, dim3(grid), dim3(256), 0, s, r); break;
-            case 4: hipLaunchKernelGGL(reduce_kernel<4>, dim3(grid), dim3(256), 0, s, r); break;
-            case 8: hipLaunchKernelGGL(reduce_kernel<8>, dim3(grid), dim3(256), 0, s, r); break;
-            default: hipLaunchKernelGGL(reduce_kernel<0>, dim3(grid), dim3(256), 0, s, r); break;
-        }
+        auto launch = [&](auto s16) {
+            constexpr bool S16 = decltype(s16)::value;
+            switch (P) {
+                case 1: hipLaunchKernelGGL((reduce_kernel<1, S16>), dim3(grid), dim3(256), 0, s, r); break;
+                case 2: hipLaunchKernelGGL((reduce_kernel<2, S16>), dim3(grid), dim3(256), 0, s, r); break;
+                case 4: hipLaunchKernelGGL((reduce_kernel<4, S16>), dim3(grid), dim3(256), 0, s, r); break;
+                case 8: hipLaunchKernelGGL((reduce_kernel<8, S16>), dim3(grid), dim3(256), 0, s, r); break;
+                default: hipLaunchKernelGGL((reduce_kernel<0, S16>), dim3(grid), dim3(256), 0, s, r); break;
+            }
+        };
+        if (bf16_slots) launch(std::true_type{});
+        else launch(std::false_type{});
         if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
     }
     return PK_OK;
@@ -494,12 +530,12 @@ pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, p
 
 pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
-                     float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases, int comm_cus, uint32_t* status, uint64_t timeout_us,
-                     void* stream) {
+                     void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
+                     void* out_shard, uint32_t phases, int comm_cus, int partial_dt, uint32_t* status,
+                     uint64_t timeout_us, void* stream) {
     if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
     return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, status, timeout_us, stream);
+                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, status, timeout_us, stream);
 }
 
 pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -511,10 +547,10 @@ pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, p
 
 pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
-                     float* partials, float* outgoing, uint32_t* flags_in, uint32_t* flags_out,
+                     void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out,
                      void* out_full, void* bcast_out, uint32_t* ar_flags_in, uint32_t* ar_flags_out,
-                     uint32_t epoch, uint32_t phases, int comm_cus, uint32_t* status, uint64_t timeout_us,
-                     void* stream) {
+                     uint32_t epoch, uint32_t phases, int comm_cus, int partial_dt, uint32_t* status,
+                     uint64_t timeout_us, void* stream) {
     if (phases == 0 || (phases & ~(PK_PHASE_ALL | PK_PHASE_WAIT))) return PK_ERR_ARG;
     if (!out_full || !ar_flags_in || !status) return PK_ERR_NULL;
     if (P > 1 && (!bcast_out || !ar_flags_out)) return PK_ERR_NULL;
@@ -528,7 +564,7 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         // the reduce phase writes rows R_rank of out_full
         uint16_t* own_rows = (uint16_t*)out_full + (int64_t)rank * (M / P) * N;
         st = gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, status, timeout_us, stream);
+                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, partial_dt, status, timeout_us, stream);
         if (st != PK_OK) return st;
     }
     if (phases & PK_PHASE_WAIT) {

@@ -17,6 +17,8 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_RANK, ERR_ARG, ERR_HIP, ERR_T
 BF16, FP8_E4M3 = 0, 1
 PHASE_GEMM, PHASE_REDUCE, PHASE_ALL, PHASE_WAIT = 1, 2, 3, 4
 AR_ROWS = 8
+PARTIAL_F32, PARTIAL_BF16 = 0, 1
+PARTIALS = {"f32": PARTIAL_F32, "bf16": PARTIAL_BF16}
 EMU_MAX_ORDER = 64
 DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
 
@@ -58,7 +60,7 @@ def lib():
             f.restype = i32
             f.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.pk_gemm_rs.restype = i32
-        L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, vp, u64, vp]
+        L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, i32, vp, u64, vp]
         L.pk_ag_gemm.restype = i32
         L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, vp, u64, vp]
         L.pk_emu_deliver_chunks.restype = i32
@@ -69,7 +71,7 @@ def lib():
         L.pk_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pk_gemm_ar.restype = i32
         L.pk_gemm_ar.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, i32,
-                                 vp, u64, vp]
+                                 i32, vp, u64, vp]
         L.pk_partition_create.restype = i32
         L.pk_partition_create.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
         L.pk_partition_destroy.restype = i32
@@ -98,6 +100,10 @@ def _dt(dtype):
     return DTYPES[dtype] if isinstance(dtype, str) else int(dtype)
 
 
+def _pdt(partial_dtype):
+    return PARTIALS[partial_dtype] if isinstance(partial_dtype, str) else int(partial_dtype)
+
+
 def _check(code, where):
     if code != OK:
         raise PkError(code, where)
@@ -124,10 +130,12 @@ def pk_ag_gemm_plan(P, M, N, K, dtype):
 
 
 def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing,
-               flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None, comm_cus=0):
+               flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None, comm_cus=0,
+               partial_dtype="f32"):
     _check(lib().pk_gemm_rs(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
-                            _ptr(out_shard), phases, comm_cus, _ptr(status), timeout_us, _stream(stream)), "pk_gemm_rs")
+                            _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), _ptr(status), timeout_us,
+                            _stream(stream)), "pk_gemm_rs")
 
 
 def pk_gemm_ar_plan(P, M, N, K, dtype):
@@ -138,11 +146,11 @@ def pk_gemm_ar_plan(P, M, N, K, dtype):
 
 def pk_gemm_ar(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in, flags_out,
                out_full, bcast_out, ar_flags_in, ar_flags_out, epoch, phases, status, timeout_us=0, stream=None,
-               comm_cus=0):
+               comm_cus=0, partial_dtype="f32"):
     _check(lib().pk_gemm_ar(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), _ptr(out_full),
                             _ptr(bcast_out), _ptr(ar_flags_in), _ptr(ar_flags_out), epoch, phases, comm_cus,
-                            _ptr(status), timeout_us, _stream(stream)), "pk_gemm_ar")
+                            _pdt(partial_dtype), _ptr(status), timeout_us, _stream(stream)), "pk_gemm_ar")
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,

@@ -28,13 +28,44 @@ def bits_of(t):
     return t.cpu().numpy().view(np.uint16)
 
 
+BF16_NAN = 0x7FC1
+
+
+def slot_poison(P, mp, N, s16):
+    """Partial slots filled with NaN: fp32, or bf16 bit patterns held in an int16 tensor."""
+    if s16:
+        return dev(np.full((P, mp, N), BF16_NAN, dtype=np.uint16).view(np.int16))
+    return torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+
+
+def slot_upload(partials, s16):
+    if s16:
+        return dev(np.ascontiguousarray(partials, dtype=np.uint16).view(np.int16))
+    return dev(partials.astype(np.float32))
+
+
+def slot_download(t, s16):
+    return bits_of(t) if s16 else t.cpu().numpy()
+
+
+def deliver_slots(P, M, N, tile_m, tile_n, staging, part, flags, epoch, order, gap_us, side, n_wg, s16):
+    """Peer slots through the emulated communicator; bf16 slots travel as fp32 pairs (N/2 columns, tile_n/2 per flag)."""
+    if s16:
+        pk.pk_emu_deliver_partials(P, M, N // 2, tile_m, tile_n // 2, staging, part, flags, epoch, order, gap_us,
+                                   stream=side, n_wg=n_wg)
+    else:
+        pk.pk_emu_deliver_partials(P, M, N, tile_m, tile_n, staging, part, flags, epoch, order, gap_us, stream=side,
+                                   n_wg=n_wg)
+
+
 def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
-                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0):
+                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0, partial_dtype="f32"):
     """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
 
     partition = (compute_stream, comm_stream) handles from pk_partition_create: the op then runs on the first and
     the emulated peers on the second.
+    partial_dtype = "bf16": `partials` holds uint16 bit patterns; outgoing / partials_after come back as uint16.
 
     deliver = "pre": peer slots and their flags are in place before the call.
     deliver = "emu": peer slots start as NaN; pk_emu_deliver_partials copies them in on a second stream,
@@ -50,7 +81,8 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
     B = elem_view(B_bits, dtype)
     sa, sb = scale_t(scale_a), scale_t(scale_b)
     out = torch.full((mp, N), -1, dtype=torch.int16, device="cuda")
-    outgoing = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+    s16 = partial_dtype == "bf16"
+    outgoing = slot_poison(P, mp, N, s16)
     flags_in = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     status = torch.zeros(4, dtype=torch.int32, device="cuda")
@@ -59,30 +91,29 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
         order = peers
     main = torch.cuda.current_stream() if partition is None else torch.cuda.ExternalStream(partition[0])
     if deliver == "pre":
-        part = dev(partials.astype(np.float32))
-        part[rank].fill_(NAN_POISON)
+        part = slot_upload(partials, s16)
+        part[rank].copy_(slot_poison(1, mp, N, s16)[0])
         for q in peers:
             flags_in[q].fill_(epoch)
         if withhold is not None:
             flags_in[withhold[0], withhold[1]] = epoch - 1
         torch.cuda.synchronize()
     else:
-        staging = dev(partials.astype(np.float32))
-        part = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+        staging = slot_upload(partials, s16)
+        part = slot_poison(P, mp, N, s16)
         torch.cuda.synchronize()
         side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
-        pk.pk_emu_deliver_partials(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch,
-                                   list(order), gap_us, stream=side, n_wg=n_wg)
+        deliver_slots(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us, side, n_wg, s16)
     pk.pk_gemm_rs(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
                   flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main,
-                  comm_cus=comm_cus)
+                  comm_cus=comm_cus, partial_dtype=partial_dtype)
     torch.cuda.synchronize()
     res = {"out_bits": bits_of(out), "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
            "status": status.cpu().numpy(), "plan": plan}
     if lazy:
         res["outgoing_t"], res["partials_t"] = outgoing, part
     else:
-        res["outgoing"], res["partials_after"] = outgoing.cpu().numpy(), part.cpu().numpy()
+        res["outgoing"], res["partials_after"] = slot_download(outgoing, s16), slot_download(part, s16)
     return res
 
 
@@ -136,7 +167,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
 
 def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, scale_a=None, scale_b=None, epoch=1,
                 deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL | pk.PHASE_WAIT,
-                withhold_rows=None):
+                withhold_rows=None, partial_dtype="f32"):
     """One pk_gemm_ar call.  partials as run_gemm_rs; peer_rows: numpy [P][M/P][N] uint16, block q != rank is what
     rank q hands out for rows R_q of out_full.
 
@@ -150,7 +181,8 @@ def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, sc
     A, B = elem_view(A_bits, dtype), elem_view(B_bits, dtype)
     sa, sb = scale_t(scale_a), scale_t(scale_b)
     poison_rows = np.full((P, mp, N), 0x7FC1, dtype=np.uint16)
-    outgoing = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+    s16 = partial_dtype == "bf16"
+    outgoing = slot_poison(P, mp, N, s16)
     bcast = dev(poison_rows.view(np.int16))
     flags_in = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
@@ -163,8 +195,8 @@ def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, sc
     main = torch.cuda.current_stream()
     peer_rows = np.ascontiguousarray(peer_rows, dtype=np.uint16)
     if deliver == "pre":
-        part = dev(partials.astype(np.float32))
-        part[rank].fill_(NAN_POISON)
+        part = slot_upload(partials, s16)
+        part[rank].copy_(slot_poison(1, mp, N, s16)[0])
         start = peer_rows.copy()
         start[rank] = 0x7FC1
         full = dev(start.view(np.int16).reshape(M, N))
@@ -175,21 +207,20 @@ def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, sc
             ar_in[withhold_rows[0], withhold_rows[1]] = epoch - 1
         torch.cuda.synchronize()
     else:
-        staging = dev(partials.astype(np.float32))
+        staging = slot_upload(partials, s16)
         staging_rows = dev(peer_rows.view(np.int16))
-        part = torch.full((P, mp, N), NAN_POISON, dtype=torch.float32, device="cuda")
+        part = slot_poison(P, mp, N, s16)
         full = dev(poison_rows.view(np.int16).reshape(M, N))
         torch.cuda.synchronize()
         side = torch.cuda.Stream()
-        pk.pk_emu_deliver_partials(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us,
-                                   stream=side)
+        deliver_slots(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us, side, 0, s16)
         # the bf16 row blocks as fp32 pairs: N/2 columns, PK_AR_ROWS x tile_n/2 per flag
         pk.pk_emu_deliver_partials(P, M, N // 2, pk.AR_ROWS, plan.tile_n // 2, staging_rows, full, ar_in, epoch,
                                    list(order), gap_us, stream=side)
     pk.pk_gemm_ar(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None, flags_in,
                   flags_out if P > 1 else None, full, bcast if P > 1 else None, ar_in, ar_out if P > 1 else None, epoch,
-                  phases, status, timeout_us, stream=main)
+                  phases, status, timeout_us, stream=main, partial_dtype=partial_dtype)
     torch.cuda.synchronize()
     return {"full_bits": bits_of(full), "bcast_bits": bits_of(bcast), "ar_in": ar_in.cpu().numpy(),
             "ar_out": ar_out.cpu().numpy(), "flags_out": flags_out.cpu().numpy(), "status": status.cpu().numpy(),
-            "outgoing": outgoing.cpu().numpy(), "plan": plan}
+            "outgoing": slot_download(outgoing, s16), "plan": plan}

@@ -62,8 +62,8 @@ def test_plan_errors(args, code):
 
 
 def _rs(P=2, rank=0, M=256, N=256, K=512, dt=pk.BF16, A=0x1000, B=0x2000, sa=None, sb=None, part=0x3000,
-        outg=0x4000, fin=0x5000, fout=0x6000, out=0x7000, phases=3, status=0x8000):
-    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, 0, status, 0, None)
+        outg=0x4000, fin=0x5000, fout=0x6000, out=0x7000, phases=3, status=0x8000, pdt=0):
+    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, 0, pdt, status, 0, None)
 
 
 def test_gemm_rs_argument_errors_launch_nothing():
@@ -83,7 +83,9 @@ def test_gemm_rs_argument_errors_launch_nothing():
     assert _rs(M=255) == pk.ERR_SHAPE
     assert _rs(dt=5) == pk.ERR_DTYPE
     assert pk.lib().pk_gemm_rs(2, 0, 256, 256, 512, pk.BF16, 0x1000, 0x2000, None, None, 0x3000, 0x4000, 0x5000, 0x6000, 1,
-                               0x7000, 3, -8, 0x8000, 0, None) == pk.ERR_ARG      # comm_cus
+                               0x7000, 3, -8, 0, 0x8000, 0, None) == pk.ERR_ARG      # comm_cus
+    assert _rs(pdt=2) == pk.ERR_DTYPE
+    assert _rs(pdt=-1) == pk.ERR_DTYPE
 
 
 def test_ag_gemm_argument_errors_launch_nothing():
@@ -129,9 +131,9 @@ def test_gemm_ar_plan_and_argument_errors_launch_nothing():
     f = pk.lib().pk_gemm_ar
 
     def ar(P=2, rank=0, M=256, N=256, K=512, full=0x9000, bc=0xA000, ai=0xB000, ao=0xC000, phases=7, status=0x8000,
-           part=0x3000):
+           part=0x3000, pdt=0):
         return f(P, rank, M, N, K, pk.BF16, 0x1000, 0x2000, None, None, part, 0x4000, 0x5000, 0x6000, full, bc, ai, ao,
-                 1, phases, 0, status, 0, None)
+                 1, phases, 0, pdt, status, 0, None)
 
     assert ar(phases=0) == pk.ERR_ARG
     assert ar(phases=8) == pk.ERR_ARG
@@ -144,6 +146,7 @@ def test_gemm_ar_plan_and_argument_errors_launch_nothing():
     assert ar(rank=2) == pk.ERR_RANK
     assert ar(M=255) == pk.ERR_SHAPE
     assert ar(part=None) == pk.ERR_NULL
+    assert ar(pdt=3) == pk.ERR_DTYPE
 
 
 def test_partition_and_probe_argument_errors_launch_nothing():
