@@ -181,9 +181,30 @@ def gather_chunks(chunks):
     return np.concatenate([np.asarray(c) for c in chunks], axis=0)
 
 
+ACTIVATIONS = ("none", "relu", "gelu_tanh", "silu")
+
+
+def activation(x, kind):
+    """The non-linearity between the two GEMMs of the tensor-parallel MLP (section 4.1 names "a non-linear
+    activation" without fixing one; these are the usual choices), elementwise in float64:
+      relu(x) = max(x, 0);  silu(x) = x / (1 + exp(-x));
+      gelu_tanh(x) = x/2 * (1 + tanh( sqrt(2/pi) * (x + 0.044715 x^3) )).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    if kind in (None, "none"):
+        return x
+    if kind == "relu":
+        return np.maximum(x, 0.0)
+    if kind == "silu":
+        return x / (1.0 + np.exp(-x))
+    if kind == "gelu_tanh":
+        return 0.5 * x * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (x + 0.044715 * x ** 3)))
+    raise ValueError(f"unknown activation {kind!r}")
+
+
 def ag_gemm(P, rank, a_gathered_bits, b_local_bits, dtype,
-            scale_a=None, scale_b=None, rows=None):
-    """One rank's all-gather + GEMM: C[:, N_rank] = A . B[:, N_rank].
+            scale_a=None, scale_b=None, rows=None, act="none"):
+    """One rank's all-gather + GEMM: C[:, N_rank] = act( A . B[:, N_rank] ).
 
     a_gathered_bits: M x K (all P chunks in place), b_local_bits: K x N/P.
     Returns a dict: C (M x N/P float64, or len(rows) x N/P), C_bf16 (uint16).
@@ -193,8 +214,21 @@ def ag_gemm(P, rank, a_gathered_bits, b_local_bits, dtype,
         raise ValueError("M must be a multiple of P")
     if not 0 <= rank < P:
         raise ValueError("rank out of range")
-    c = local_product(a_gathered_bits, b_local_bits, dtype, scale_a, scale_b, rows=rows)
+    c = activation(local_product(a_gathered_bits, b_local_bits, dtype, scale_a, scale_b, rows=rows), act)
     return {"C": c, "C_bf16": codec.bf16_encode(c)}
+
+
+def mlp_block(P, rank, x_gathered_bits, w1_local_bits, w2_local_bits, partials, act="silu"):
+    """The tensor-parallel MLP of section 4.1 on rank `rank`, bf16 throughout:
+        H = bf16( act( X . W1[:, I_rank] ) )          all-gather + GEMM, column-sharded weights (M x I/P)
+        out = sum_p partial_p,  own partial = H . W2[I_rank, :]    GEMM + reduce-scatter, row-sharded weights
+    H is rounded to bf16 between the two GEMMs because it is stored as the second GEMM's operand.
+    Returns a dict: H_bf16 (uint16), and the gemm_rs result on it (own, outgoing, out, out_bf16).
+    """
+    h = ag_gemm(P, rank, x_gathered_bits, w1_local_bits, "bf16", act=act)
+    res = gemm_rs(P, rank, h["C_bf16"], w2_local_bits, "bf16", partials)
+    res["H_bf16"] = h["C_bf16"]
+    return res
 
 
 def abs_product(a_bits, b_bits, dtype, scale_a=None, scale_b=None, rows=None):

@@ -213,6 +213,55 @@ def test_bf16_partial_slots_integer_problem_equals_fp32_slots(P, M, N, K):
         assert np.array_equal(codec.bf16_decode(ar["bcast_bf16"]), full[r * mp:(r + 1) * mp])
 
 
+def test_activation_closed_forms_and_identities():
+    x = np.linspace(-6, 6, 97)
+    for kind in ("silu", "gelu_tanh"):
+        y = tp_gemm.activation(x, kind)
+        assert np.allclose(y - tp_gemm.activation(-x, kind), x, rtol=0, atol=1e-15)      # f(x) - f(-x) = x
+        assert tp_gemm.activation(0.0, kind) == 0.0
+        assert np.all(np.diff(y[x >= 0]) > 0)                                            # increasing on x >= 0
+        assert abs(tp_gemm.activation(30.0, kind) - 30.0) < 1e-9 and abs(tp_gemm.activation(-30.0, kind)) < 1e-9
+    assert abs(tp_gemm.activation(1.0, "silu") - 0.7310585786300049) < 1e-15             # 1 / (1 + e^-1)
+    assert abs(tp_gemm.activation(1.0, "gelu_tanh") - 0.8411919906082768) < 1e-12        # published value of the tanh form
+    # the tanh form stays within 5e-4 of x * Phi(x) (standard normal distribution function)
+    from math import erf, sqrt
+    exact = np.array([v * 0.5 * (1.0 + erf(v / sqrt(2.0))) for v in x])
+    assert np.max(np.abs(tp_gemm.activation(x, "gelu_tanh") - exact)) < 5e-4
+    assert np.array_equal(tp_gemm.activation(np.array([-2.0, 0.0, 3.0]), "relu"), [0.0, 0.0, 3.0])
+    assert np.array_equal(tp_gemm.activation(x, "none"), x) and np.array_equal(tp_gemm.activation(x, None), x)
+    with pytest.raises(ValueError):
+        tp_gemm.activation(x, "tanh")
+
+
+def test_mlp_block_chains_the_two_ops_through_bf16():
+    """Integer problem with relu: H and the output are exact, so the chain can be brute-forced."""
+    P, M, I, D = 2, 4, 6, 3                    # X: M x D gathered, W1: D x I, W2: I x D
+    X = wl.small_int_matrix((M, D), 51, 1)
+    W1 = wl.small_int_matrix((D, I), 51, 2)
+    W2 = wl.small_int_matrix((I, D), 51, 3)
+    ip, mp = I // P, M // P
+    H = [[max(v, 0) for v in row] for row in _brute_int(X, W1)]                            # relu, integers
+    full = np.array(_brute_int(np.array(H, dtype=np.float32), W2), dtype=np.float64)
+    for r in range(P):
+        cols = slice(r * ip, (r + 1) * ip)
+        partials = np.zeros((P, mp, D), np.float32)
+        for q in range(P):
+            if q != r:
+                cq = slice(q * ip, (q + 1) * ip)
+                hq = np.array(H, dtype=np.float32)[:, cq]
+                partials[q] = np.array(_brute_int(hq, W2[cq, :]), dtype=np.float32)[r * mp:(r + 1) * mp]
+        res = tp_gemm.mlp_block(P, r, _int_bits(X, "bf16"), _int_bits(W1[:, cols], "bf16"), _int_bits(W2[cols, :], "bf16"),
+                                partials, act="relu")
+        assert np.array_equal(codec.bf16_decode(res["H_bf16"]), np.array(H, dtype=np.float64)[:, cols])
+        assert np.array_equal(res["out"], full[r * mp:(r + 1) * mp])
+    # H is rounded to bf16 before the second GEMM: 1 + 2^-8 (a tie) becomes 1.0
+    x = codec.bf16_encode(np.array([[1.0, 2.0 ** -8]]))
+    w1 = codec.bf16_encode(np.array([[1.0], [1.0]]))
+    w2 = codec.bf16_encode(np.array([[1.0]]))
+    res = tp_gemm.mlp_block(1, 0, x, w1, w2, np.zeros((1, 1, 1), np.float32), act="none")
+    assert res["H_bf16"][0, 0] == 0x3F80 and res["out"][0, 0] == 1.0
+
+
 def test_linearity_and_shard_concatenation_random_bf16():
     """Sum over ranks of A[:,K_p].B[K_p,:] equals the unsharded GEMM (to float64 rounding),
     and the P reduced shards stacked give the whole product."""
