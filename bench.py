@@ -417,6 +417,21 @@ def extras(pk, wl, torch, np, L):
                                "frac_of_hbm_peak": round(bytes5 / (t5 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                "gemm_phase_ms": round(t5g, 4), "gemm_phase_TFLOP/s": round(c5.flops / (t5g * 1e-3) / 1e12, 1),
                                "reduce_phase_ms": round(t5r, 4), "reduce_phase_GB/s": round(red5 / (t5r * 1e-3) / 1e9, 1)}
+    # the MLP block of the paper's section 4.1 with real data flow: AG + GEMM (cfg4) with SiLU fused into its epilogue writes
+    # H (8192 x 3584 bf16), which is the local operand of GEMM + RS (cfg3)
+    H = torch.zeros((c4.M, c4.N // c4.P), dtype=torch.int16, device="cuda")
+    epm = [7 * 10 ** 6]
+
+    def mlp():
+        epm[0] += 1
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, L["chunk_flags"], 1, H,
+                      L["status"], act="silu")
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, H, L["B3"], None, None, L["part"], L["outgoing"],
+                      L["flags_in"], L["flags_out"], epm[0], L["out3"], pk.PHASE_ALL, L["status"])
+    t_mlp = timeit(mlp)
+    out["mlp_block_cfg4_silu_cfg3"] = {"ms": round(t_mlp, 4),
+                                       "TFLOP/s": round((c3.flops + c4.flops) / (t_mlp * 1e-3) / 1e12, 1)}
+
     # the paper's own element size for communicated tiles (s = 2): bf16 partial slots halve scatter and reduce traffic
     out["bf16_partial_slots"] = {}
     for name, c, A, B, sa, sb, part32, fin, fout, o in (("cfg3", c3, L["A3"], L["B3"], None, None, L["part"], L["flags_in"],

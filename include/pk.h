@@ -61,6 +61,15 @@ typedef enum {
                               rounded to bf16 once before the fp32 sum */
 } pk_partial_dtype;
 
+/* non-linearity fused into pk_ag_gemm's epilogue (paper section 4.1: AG + GEMM, "a non-linear activation", GEMM + RS);
+ * evaluated in fp32 on the accumulator, before the rounding to bf16 */
+typedef enum {
+    PK_ACT_NONE = 0,
+    PK_ACT_RELU = 1,        /* max(x, 0) */
+    PK_ACT_GELU_TANH = 2,   /* x/2 * (1 + tanh(sqrt(2/pi) * (x + 0.044715 x^3))) */
+    PK_ACT_SILU = 3         /* x / (1 + exp(-x)) */
+} pk_activation;
+
 /* phases of pk_gemm_rs (bit mask) */
 #define PK_PHASE_GEMM   1u   /* local GEMM + scatter of finished tiles + per-tile signal */
 #define PK_PHASE_REDUCE 2u   /* wait for the P partials of each own tile, sum, round, store */
@@ -156,7 +165,7 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  * gathered, weights column-sharded; section 3.1.3 "inter-SM overlapping": the chunks are moved by dedicated
  * communicator workers while the compute workers wait on a per-chunk flag before loading).
  *
- *   C_local = bf16( A_gathered . B_local )      (M x N/P; x scale_a*scale_b for fp8)
+ *   C_local = bf16( act( A_gathered . B_local ) )   (M x N/P; x scale_a*scale_b for fp8; act: pk_activation)
  *
  *   A_gathered  M x K   rows R_q = chunk q.  Chunk `rank` is valid at the call; chunk q != rank is valid
  *                       once chunk_flags[q] has reached `epoch`.
@@ -177,7 +186,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      const void* A_gathered, const void* B_local,
                      const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch,
-                     void* C_local, int comm_cus,
+                     void* C_local, int comm_cus, int activation /* pk_activation */,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*

@@ -61,6 +61,7 @@ struct GemmArgs {
     // all-gather epilogue
     uint16_t* C;              // (P*rows_per_shard) x n bf16
     const uint32_t* chunk_flags;
+    int32_t act;              // pk_activation applied to the accumulator before the bf16 rounding (all-gather mode)
     const float* scale_a;     // fp8 only
     const float* scale_b;
     uint32_t epoch;
@@ -195,6 +196,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     const int G = g.grp_tile_rows * g.tiles_n;
     float scale = 1.f;
     if constexpr (FP8) scale = g.scale_a[0] * g.scale_b[0];
+    // the non-linearity between the two GEMMs of the MLP (paper section 4.1), fused into the all-gather epilogue
+    auto activate = [&](float x) -> float {
+        switch (g.act) {
+            case PK_ACT_RELU: return fmaxf(x, 0.f);
+            case PK_ACT_GELU_TANH: return 0.5f * x * (1.f + tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x)));
+            case PK_ACT_SILU: return x / (1.f + expf(-x));
+            default: return x;
+        }
+    };
 
     auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
         if constexpr (EPI != EPI_AG) {
@@ -370,8 +380,15 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                                     *(PK_LDS f32x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16)) = val;
                                 } else {
                                     const int ch = colw >> 3;                  // 16-byte chunk (8 bf16)
-                                    bf16x4 val = {(__bf16)(acc[ti][tj][4 * b] * scale), (__bf16)(acc[ti][tj][4 * b + 1] * scale),
-                                                  (__bf16)(acc[ti][tj][4 * b + 2] * scale), (__bf16)(acc[ti][tj][4 * b + 3] * scale)};
+                                    float x0 = acc[ti][tj][4 * b] * scale, x1 = acc[ti][tj][4 * b + 1] * scale,
+                                          x2 = acc[ti][tj][4 * b + 2] * scale, x3 = acc[ti][tj][4 * b + 3] * scale;
+                                    if constexpr (EPI == EPI_AG) {
+                                        x0 = activate(x0);
+                                        x1 = activate(x1);
+                                        x2 = activate(x2);
+                                        x3 = activate(x3);
+                                    }
+                                    bf16x4 val = {(__bf16)x0, (__bf16)x1, (__bf16)x2, (__bf16)x3};
                                     *(PK_LDS bf16x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16) + (h * 8)) = val;
                                 }
                             }

@@ -578,13 +578,14 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
 
 pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
-                     const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus,
+                     const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
                      uint32_t* status, uint64_t timeout_us, void* stream) {
     pk_plan pl;
     pk_status st = make_plan(P, M, N, K, dt, false, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
     if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
+    if (activation < PK_ACT_NONE || activation > PK_ACT_SILU) return PK_ERR_ARG;
     const bool fp8 = dt == PK_FP8_E4M3;
     if (!A_gathered || !B_local || !C_local || !status) return PK_ERR_NULL;
     if (P > 1 && !chunk_flags) return PK_ERR_NULL;
@@ -605,6 +606,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
     a.grp_tile_rows = pl.tiles_m;
     a.n_groups = P;
     a.group0 = rank;
+    a.act = activation;
     const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
     a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
     a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);

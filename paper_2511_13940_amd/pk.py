@@ -17,6 +17,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_RANK, ERR_ARG, ERR_HIP, ERR_T
 BF16, FP8_E4M3 = 0, 1
 PHASE_GEMM, PHASE_REDUCE, PHASE_ALL, PHASE_WAIT = 1, 2, 3, 4
 AR_ROWS = 8
+ACTIVATIONS = {"none": 0, "relu": 1, "gelu_tanh": 2, "silu": 3}
 PARTIAL_F32, PARTIAL_BF16 = 0, 1
 PARTIALS = {"f32": PARTIAL_F32, "bf16": PARTIAL_BF16}
 EMU_MAX_ORDER = 64
@@ -62,7 +63,7 @@ def lib():
         L.pk_gemm_rs.restype = i32
         L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, i32, vp, u64, vp]
         L.pk_ag_gemm.restype = i32
-        L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, vp, u64, vp]
+        L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, i32, vp, u64, vp]
         L.pk_emu_deliver_chunks.restype = i32
         L.pk_emu_deliver_chunks.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp, vp]
         L.pk_emu_deliver_partials.restype = i32
@@ -154,9 +155,10 @@ def pk_gemm_ar(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, part
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
-               C_local, status, timeout_us=0, stream=None, comm_cus=0):
+               C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none"):
     _check(lib().pk_ag_gemm(P, rank, M, N, K, _dt(dtype), _ptr(A_gathered), _ptr(B_local), _ptr(scale_a),
-                            _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus, _ptr(status),
+                            _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus,
+                            ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(status),
                             timeout_us, _stream(stream)), "pk_ag_gemm")
 
 

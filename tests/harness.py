@@ -119,7 +119,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
 
 def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None, fetch_A=True,
-                comm_cus=0, n_wg=0, partition=None):
+                comm_cus=0, n_wg=0, partition=None, act="none"):
     """One pk_ag_gemm call.  chunks: list of P numpy bit arrays (M/P x K).
 
     deliver = "pre": every chunk is in A_gathered with its flag set before the call.
@@ -159,7 +159,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
         pk.pk_emu_deliver_chunks(P, M, K, elem, staging, A, flags, epoch, list(order), gap_us, counters, stream=side,
                                  n_wg=n_wg)
     pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,
-                  timeout_us, stream=main, comm_cus=comm_cus)
+                  timeout_us, stream=main, comm_cus=comm_cus, act=act)
     torch.cuda.synchronize()
     return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy() if fetch_A else None,
             "flags": flags.cpu().numpy()}

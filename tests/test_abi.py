@@ -92,8 +92,8 @@ def test_ag_gemm_argument_errors_launch_nothing():
     f = pk.lib().pk_ag_gemm
 
     def ag(P=4, rank=0, M=2048, N=4096, K=2048, dt=pk.BF16, A=0x1000, B=0x2000, flags=0x3000, C=0x4000, status=0x5000,
-           comm=0):
-        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, comm, status, 0, None)
+           comm=0, act=0):
+        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, comm, act, status, 0, None)
 
     assert ag(rank=4) == pk.ERR_RANK
     assert ag(N=4098) == pk.ERR_SHAPE        # N % P
@@ -104,6 +104,8 @@ def test_ag_gemm_argument_errors_launch_nothing():
     assert ag(C=0x4002) == pk.ERR_ALIGN
     assert ag(dt=pk.FP8_E4M3) == pk.ERR_DTYPE
     assert ag(comm=-1) == pk.ERR_ARG
+    assert ag(act=4) == pk.ERR_ARG
+    assert ag(act=-1) == pk.ERR_ARG
 
 
 def test_emulator_argument_errors_launch_nothing():

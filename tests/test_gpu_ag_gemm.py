@@ -118,3 +118,62 @@ def test_missing_chunk_times_out_instead_of_hanging():
     keep = np.r_[0:2 * mp, 3 * mp:M]
     assert gate_err(got[keep], ref[keep]) <= GATE["bf16"]          # the other chunks' tiles were computed
     assert np.all(res["C_bits"][2 * mp:3 * mp] == 0xFFFF)          # the withheld chunk's rows were left alone
+
+
+@pytest.mark.parametrize("act", ["relu", "gelu_tanh", "silu"])
+@pytest.mark.parametrize("dtype,P,M,N,K,rank", [
+    ("bf16", 2, 2 * 200, 2 * 264, 256, 1),      # ragged 128-tiles
+    ("bf16", 2, 4096, 2 * 2048, 256, 0),        # 256-tiles
+    ("fp8", 2, 512, 2 * 256, 256, 1),
+])
+def test_fused_activation(act, dtype, P, M, N, K, rank):
+    """act(A.B) in the epilogue: fp32 evaluation on the accumulator, then one rounding to bf16.  The inputs are scaled up
+    so that the pre-activations spread over a few units (the non-linear range)."""
+    inp = wl.ag_gemm_inputs(P, M, N, K, dtype, rank, seed=31)
+    if dtype == "bf16":          # x 16 on one operand: exact in bf16, pre-activations ~ N(0, 1)
+        inp["B_local"] = codec.bf16_encode(codec.bf16_decode(inp["B_local"]) * 16.0)
+    res = hz.run_ag_gemm(P, rank, M, N, K, dtype, inp["chunks"], inp["B_local"], inp["scale_a"], inp["scale_b"], act=act)
+    assert res["status"][0] == 0
+    A = tp_gemm.gather_chunks(inp["chunks"])
+    ref = tp_gemm.ag_gemm(P, rank, A, inp["B_local"], dtype, inp["scale_a"], inp["scale_b"], act=act)["C"]
+    mag = tp_gemm.abs_product(A, inp["B_local"], dtype, inp["scale_a"], inp["scale_b"])
+    got = codec.bf16_decode(res["C_bits"])
+    assert not np.isnan(got).any()
+    assert gate_err(got, ref) <= GATE[dtype]
+    # the activations are 1.13-Lipschitz: the accumulation error passes through at most that much amplified; the fp32
+    # evaluation of exp / tanh adds a few fp32 ulps of the result and of x
+    pre = tp_gemm.ag_gemm(P, rank, A, inp["B_local"], dtype, inp["scale_a"], inp["scale_b"])["C"]
+    bound = 1.13 * 2 * K * U32 * mag + 2.0 ** -8 * np.abs(ref) + 16 * U32 * (np.abs(pre) + 1.0) + 2.0 ** -133
+    assert np.all(np.abs(got - ref) <= bound)
+    if act == "relu":
+        assert np.all(got >= 0) and np.any(got == 0) and np.any(got > 0)
+
+
+def test_mlp_block_chain_matches_the_oracle():
+    """AG + GEMM with fused SiLU, its bf16 output fed to GEMM + RS as the local operand (paper section 4.1), against the
+    oracle's chained definition."""
+    P, rank, M, D, I = 4, 1, 2048, 1024, 4096
+    rng_seed = 41
+    inp1 = wl.ag_gemm_inputs(P, M, I, D, "bf16", rank, seed=rng_seed)                       # X chunks, W1[:, I_rank]: D x I/P
+    inp1["B_local"] = codec.bf16_encode(codec.bf16_decode(inp1["B_local"]) * 16.0)
+    inp2 = wl.gemm_rs_inputs(P, M, D, I, "bf16", rank, seed=rng_seed + 1)                   # W2[I_rank, :]: I/P x D, peers' partials
+    h = hz.run_ag_gemm(P, rank, M, I, D, "bf16", inp1["chunks"], inp1["B_local"], act="silu")
+    assert h["status"][0] == 0
+    res = hz.run_gemm_rs(P, rank, M, D, I, "bf16", h["C_bits"], inp2["B_local"], inp2["partials"])
+    assert res["status"][0] == 0
+    X = tp_gemm.gather_chunks(inp1["chunks"])
+    ref = tp_gemm.mlp_block(P, rank, X, inp1["B_local"], inp2["B_local"], inp2["partials"], act="silu")
+    # H: a few elements may round to the neighbouring bf16 value (fp32 vs float64 evaluation next to a tie)
+    hg, hr = codec.bf16_decode(h["C_bits"]), codec.bf16_decode(ref["H_bf16"])
+    assert np.mean(h["C_bits"] != ref["H_bf16"]) < 0.02
+    mag1 = tp_gemm.abs_product(X, inp1["B_local"], "bf16")
+    assert np.all(np.abs(hg - hr) <= 1.13 * 2 * D * U32 * mag1 + 2.0 ** -7 * np.abs(hr) + 2.0 ** -133)
+    got = codec.bf16_decode(res["out_bits"])
+    assert gate_err(got, ref["out"]) <= GATE["bf16"]
+    # second GEMM on the GPU's own H: exact parity chain (no tie ambiguity)
+    ref2 = tp_gemm.gemm_rs(P, rank, h["C_bits"], inp2["B_local"], "bf16", inp2["partials"])
+    mag = tp_gemm.abs_product(h["C_bits"], inp2["B_local"], "bf16")
+    mp = M // P
+    slot_mag = np.abs(ref2["outgoing"][rank]) + sum(np.abs(inp2["partials"][q].astype(np.float64)) for q in range(P) if q != rank)
+    bound = 2 * (I // P) * U32 * mag[rank * mp:(rank + 1) * mp] + P * U32 * slot_mag + 2.0 ** -8 * np.abs(ref2["out"]) + 2.0 ** -133
+    assert np.all(np.abs(got - ref2["out"]) <= bound)
