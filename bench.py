@@ -352,6 +352,26 @@ def extras(pk, wl, torch, np, L):
         pk.pk_partition_destroy(h_comp, h_comm)
         return res
 
+    # chunks moved by device-to-device copies + stream flag writes (no communicator workgroups), GEMM on all compute units
+    side2 = torch.cuda.Stream()
+    flags_dma = torch.zeros(c4.P, dtype=torch.int32, device="cuda")
+    done2 = torch.cuda.Event()
+    epd = [8 * 10 ** 6]
+
+    def ag_live_dma():
+        epd[0] += 1
+        done2.record(stream)
+        side2.wait_event(done2)
+        pk.pk_emu_deliver_chunks_dma(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_dma, epd[0], order, stream=side2)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_dma, epd[0], L["C4"],
+                      L["status"])
+        stream.wait_stream(side2)
+    t_dma = timeit(ag_live_dma)
+    t_dma_alone = timeit(lambda: pk.pk_emu_deliver_chunks_dma(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_dma, 1, order,
+                                                               stream=stream))
+    out["ag_gemm_live_copy_engine"] = {"ms_live_ring_arrival": round(t_dma, 4), "ms_copies_alone": round(t_dma_alone, 4),
+                                       "TFLOP/s_live": round(c4.flops / (t_dma * 1e-3) / 1e12, 1)}
+
     out.update(live(32))
     out["comm_cus_sweep"] = {}
     for cc in (16, 64):

@@ -211,6 +211,13 @@ pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes,
                                 uint32_t* chunk_flags, uint32_t epoch,
                                 const int* order /* host */, int n_order, uint32_t gap_us, int n_wg,
                                 uint32_t* counters, void* stream);
+/* The same delivery of chunks without communicator workgroups (paper section 3.1.1, host-initiated copy engine
+ * transfers): one device-to-device copy per chunk on `stream`, each followed by a stream memory operation that writes the
+ * chunk's flag.  No compute unit is taken from the consumer; granularity is a whole chunk. */
+pk_status pk_emu_deliver_chunks_dma(int P, int64_t M, int64_t K, int elem_bytes,
+                                    const void* staging, void* A_gathered,
+                                    uint32_t* chunk_flags, uint32_t epoch,
+                                    const int* order /* host */, int n_order, void* stream);
 pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n,
                                   const float* staging, float* partials,
                                   uint32_t* flags_in, uint32_t epoch,

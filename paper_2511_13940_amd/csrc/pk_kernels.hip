@@ -653,6 +653,27 @@ pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes, con
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }
 
+pk_status pk_emu_deliver_chunks_dma(int P, int64_t M, int64_t K, int elem_bytes, const void* staging, void* A_gathered,
+                                    uint32_t* chunk_flags, uint32_t epoch, const int* order, int n_order, void* stream) {
+    if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || K < 1 || M % P) return PK_ERR_SHAPE;
+    if (elem_bytes != 1 && elem_bytes != 2) return PK_ERR_DTYPE;
+    if (!staging || !A_gathered || !chunk_flags) return PK_ERR_NULL;
+    const int64_t chunk_bytes = (M / P) * K * elem_bytes;
+    EmuOrder o;
+    pk_status st = make_order(order, n_order, P, &o);
+    if (st != PK_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < o.n; ++i) {
+        const int64_t off = (int64_t)o.q[i] * chunk_bytes;
+        // stream order puts the flag write behind the completed copy
+        if (hipMemcpyAsync((char*)A_gathered + off, (const char*)staging + off, (size_t)chunk_bytes, hipMemcpyDeviceToDevice,
+                           s) != hipSuccess)
+            return PK_ERR_HIP;
+        if (hipStreamWriteValue32(s, chunk_flags + o.q[i], epoch, 0) != hipSuccess) return PK_ERR_HIP;
+    }
+    return PK_OK;
+}
+
 pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n, const float* staging,
                                   float* partials, uint32_t* flags_in, uint32_t epoch, const int* order, int n_order,
                                   uint32_t gap_us, int n_wg, void* stream) {

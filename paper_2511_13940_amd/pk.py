@@ -25,7 +25,7 @@ DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
 
 EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_ag_gemm_plan", "pk_ag_gemm",
            "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy",
-           "pk_gemm_ar_plan", "pk_gemm_ar"]
+           "pk_gemm_ar_plan", "pk_gemm_ar", "pk_emu_deliver_chunks_dma"]
 
 
 class Plan(ctypes.Structure):
@@ -73,6 +73,8 @@ def lib():
         L.pk_gemm_ar.restype = i32
         L.pk_gemm_ar.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, i32,
                                  i32, vp, u64, vp]
+        L.pk_emu_deliver_chunks_dma.restype = i32
+        L.pk_emu_deliver_chunks_dma.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, vp]
         L.pk_partition_create.restype = i32
         L.pk_partition_create.argtypes = [i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
         L.pk_partition_destroy.restype = i32
@@ -173,6 +175,12 @@ def pk_emu_deliver_chunks(P, M, K, elem_bytes, staging, A_gathered, chunk_flags,
     _check(lib().pk_emu_deliver_chunks(P, M, K, elem_bytes, _ptr(staging), _ptr(A_gathered), _ptr(chunk_flags),
                                        epoch, arr, n, gap_us, n_wg, _ptr(counters), _stream(stream)),
            "pk_emu_deliver_chunks")
+
+
+def pk_emu_deliver_chunks_dma(P, M, K, elem_bytes, staging, A_gathered, chunk_flags, epoch, order, stream=None):
+    arr, n = _order(order)
+    _check(lib().pk_emu_deliver_chunks_dma(P, M, K, elem_bytes, _ptr(staging), _ptr(A_gathered), _ptr(chunk_flags), epoch,
+                                           arr, n, _stream(stream)), "pk_emu_deliver_chunks_dma")
 
 
 def pk_emu_deliver_partials(P, M, N, tile_m, tile_n, staging, partials, flags_in, epoch, order, gap_us,

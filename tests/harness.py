@@ -125,6 +125,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
     deliver = "pre": every chunk is in A_gathered with its flag set before the call.
     deliver = "emu": only the own chunk is in place; the others are filled with a poison pattern and
                      pk_emu_deliver_chunks copies them in on a second stream in `order`.
+    deliver = "dma": the same through pk_emu_deliver_chunks_dma (copies + stream flag writes, no workgroups).
     withhold: a chunk index whose flag is never set ("pre" only).
     """
     mp = M // P
@@ -156,8 +157,11 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
         counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
         torch.cuda.synchronize()
         side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
-        pk.pk_emu_deliver_chunks(P, M, K, elem, staging, A, flags, epoch, list(order), gap_us, counters, stream=side,
-                                 n_wg=n_wg)
+        if deliver == "dma":
+            pk.pk_emu_deliver_chunks_dma(P, M, K, elem, staging, A, flags, epoch, list(order), stream=side)
+        else:
+            pk.pk_emu_deliver_chunks(P, M, K, elem, staging, A, flags, epoch, list(order), gap_us, counters, stream=side,
+                                     n_wg=n_wg)
     pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,
                   timeout_us, stream=main, comm_cus=comm_cus, act=act)
     torch.cuda.synchronize()

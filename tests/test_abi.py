@@ -118,6 +118,9 @@ def test_emulator_argument_errors_launch_nothing():
     assert L.pk_emu_deliver_chunks(4, 2048, 2048, 4, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, 0x4000, None) == pk.ERR_DTYPE
     assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, None, 0x2000, 0x3000, 1, order, 3, 0, 0, 0x4000, None) == pk.ERR_NULL
     assert L.pk_emu_deliver_chunks(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0, 0x4000, None) == pk.OK
+    assert L.pk_emu_deliver_chunks_dma(4, 2048, 2048, 2, None, 0x2000, 0x3000, 1, order, 3, None) == pk.ERR_NULL
+    assert L.pk_emu_deliver_chunks_dma(4, 2047, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, None) == pk.ERR_SHAPE
+    assert L.pk_emu_deliver_chunks_dma(4, 2048, 2048, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, None) == pk.OK
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 65, 0, 0, None) == pk.ERR_ARG
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 130, 0x1000, 0x2000, 0x3000, 1, order, 3, 0, 0, None) == pk.ERR_ARG
     assert L.pk_emu_deliver_partials(4, 2048, 2048, 128, 128, 0x1000, 0x2000, 0x3000, 1, order, 0, 0, 0, None) == pk.OK

@@ -177,3 +177,21 @@ def test_mlp_block_chain_matches_the_oracle():
     slot_mag = np.abs(ref2["outgoing"][rank]) + sum(np.abs(inp2["partials"][q].astype(np.float64)) for q in range(P) if q != rank)
     bound = 2 * (I // P) * U32 * mag[rank * mp:(rank + 1) * mp] + P * U32 * slot_mag + 2.0 ** -8 * np.abs(ref2["out"]) + 2.0 ** -133
     assert np.all(np.abs(got - ref2["out"]) <= bound)
+
+
+def test_chunks_delivered_by_copies_and_stream_flag_writes():
+    """Chunks moved by device-to-device copies with a stream memory operation per flag (no communicator workgroups),
+    into poisoned rows while the GEMM runs on every compute unit: bit-identical to the pre-landed run."""
+    c = wl.CONFIGS["cfg2"]
+    rank = 3
+    inp = wl.ag_gemm_inputs(c.P, c.M, c.N, c.K, c.dtype, rank, seed=2)
+    base = hz.run_ag_gemm(c.P, rank, c.M, c.N, c.K, c.dtype, inp["chunks"], inp["B_local"])
+    check_ag(c.P, rank, c.dtype, inp, base, c.K)
+    full = tp_gemm.gather_chunks(inp["chunks"])
+    for i, order in enumerate([[0, 1, 2], [2, 0, 1]]):
+        res = hz.run_ag_gemm(c.P, rank, c.M, c.N, c.K, c.dtype, inp["chunks"], inp["B_local"], deliver="dma",
+                             order=order, epoch=i + 1)
+        assert res["status"][0] == 0
+        assert np.array_equal(res["C_bits"], base["C_bits"])
+        assert np.array_equal(res["A_after"].view(np.uint16), full)
+        assert np.all(res["flags"][order] == i + 1)
