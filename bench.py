@@ -269,6 +269,17 @@ def extras(pk, wl, torch, np, L):
     out["table3_style"]["gemm_TFLOP/s"] = round(c3.flops / (t_gemm * 1e-3) / 1e12, 1)
     out["table3_style"]["library_gemm_TFLOP/s"] = round(c3.flops / (t_lib * 1e-3) / 1e12, 1)
 
+    # the same bare GEMM on operands without bit activity (all 1.0): what the kernel's instruction schedule delivers when
+    # data-dependent power does not hold the clock down
+    ones_a = torch.full((m, k), 0x3F80, dtype=torch.int16, device="cuda")
+    ones_b = torch.full((k, n), 0x3F80, dtype=torch.int16, device="cuda")
+    t_ones = timeit(lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", ones_a, ones_b, None, None, None, 1, Cg, L["status"]))
+    t_lib_ones = timeit(lambda: torch.matmul(ones_a.view(torch.bfloat16), ones_b.view(torch.bfloat16), out=Cl))
+    out["table3_style"]["gemm_constant_operands_ms"] = round(t_ones, 4)
+    out["table3_style"]["gemm_constant_operands_TFLOP/s"] = round(c3.flops / (t_ones * 1e-3) / 1e12, 1)
+    out["table3_style"]["library_gemm_constant_operands_TFLOP/s"] = round(c3.flops / (t_lib_ones * 1e-3) / 1e12, 1)
+    del ones_a, ones_b
+
     # gather phase alone: the emulated communicator moving the 7 peer chunks (read + write), by workgroup count
     staging = L["A4"].clone()
     counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
