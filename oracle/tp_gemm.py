@@ -112,6 +112,32 @@ def gemm_rs(P, rank, a_local_bits, b_local_bits, dtype, partials,
             "out_bf16": codec.bf16_encode(out)}
 
 
+def gemm_rs_cols(P, rank, a_local_bits, b_local_bits, dtype, partials,
+                 scale_a=None, scale_b=None, partial_dtype="f32"):
+    """GEMM + reduce-scatter along the LAST dimension (appendix "Additional
+    collective performance": reduce-scatter along the tensor dimension, whose
+    pieces are not contiguous in memory).  Same operands as gemm_rs; rank q owns
+    the column block N_q = [q*N/P, (q+1)*N/P) of every row:
+        out[i, j'] = sum_{p<P} (A[:, K_p] . B[K_p, :])[i, rank*N/P + j']      (M x N/P).
+    partials: [P][M][N/P]; slot q != rank is what rank q sent, slot `rank` ignored.
+    Returns own (M x N), outgoing ([P][M][N/P]: slot q = columns N_q of own),
+    out (M x N/P float64), out_bf16.
+    """
+    own = local_product(a_local_bits, b_local_bits, dtype, scale_a, scale_b)
+    M, N = own.shape
+    if N % P:
+        raise ValueError("N must be a multiple of P")
+    np_ = N // P
+    slots = _slot_values(partials, partial_dtype, (P, M, np_))
+    outgoing = np.stack([own[:, q * np_:(q + 1) * np_] for q in range(P)])
+    mine = outgoing[rank] if partial_dtype == "f32" else codec.bf16_round(outgoing[rank])
+    out = np.zeros((M, np_), dtype=np.float64)
+    for p in range(P):
+        out += mine if p == rank else slots[p]
+    return {"own": own, "outgoing": outgoing, "out": out,
+            "out_bf16": codec.bf16_encode(out)}
+
+
 def gemm_rs_rows(P, rank, a_local_bits, b_local_bits, dtype, partials, rows,
                  scale_a=None, scale_b=None, partial_dtype="f32"):
     """The same result restricted to the global rows `rows` of the local product.

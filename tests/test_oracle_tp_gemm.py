@@ -213,6 +213,37 @@ def test_bf16_partial_slots_integer_problem_equals_fp32_slots(P, M, N, K):
         assert np.array_equal(codec.bf16_decode(ar["bcast_bf16"]), full[r * mp:(r + 1) * mp])
 
 
+@pytest.mark.parametrize("P,M,N,K", [(2, 3, 4, 6), (3, 5, 6, 9), (4, 2, 8, 8)])
+def test_gemm_rs_cols_integer_brute_force_all_ranks(P, M, N, K):
+    """Last-dimension scatter on one global integer problem with true partials: rank r ends with the column block
+    N_r of the unsharded product, the blocks side by side give the whole product, and slot q of `outgoing` is the
+    column block N_q of the local product."""
+    A = wl.small_int_matrix((M, K), 61, 1)
+    B = wl.small_int_matrix((K, N), 61, 2)
+    full = np.array(_brute_int(A, B), dtype=np.float64)
+    kp, np_ = K // P, N // P
+    local = [np.array(_brute_int(A[:, r * kp:(r + 1) * kp], B[r * kp:(r + 1) * kp, :]), dtype=np.float64)
+             for r in range(P)]
+    blocks = []
+    for r in range(P):
+        partials = np.zeros((P, M, np_), dtype=np.float32)
+        for q in range(P):
+            if q != r:
+                partials[q] = local[q][:, r * np_:(r + 1) * np_]
+        partials[r] = -777.0                                      # must be ignored
+        res = tp_gemm.gemm_rs_cols(P, r, _int_bits(A[:, r * kp:(r + 1) * kp], "bf16"),
+                                   _int_bits(B[r * kp:(r + 1) * kp, :], "bf16"), "bf16", partials)
+        assert np.array_equal(res["own"], local[r])
+        for q in range(P):
+            assert np.array_equal(res["outgoing"][q], local[r][:, q * np_:(q + 1) * np_])
+        assert np.array_equal(res["out"], full[:, r * np_:(r + 1) * np_])
+        blocks.append(codec.bf16_decode(res["out_bf16"]))
+    assert np.array_equal(np.concatenate(blocks, axis=1), full)
+    with pytest.raises(ValueError):
+        tp_gemm.gemm_rs_cols(P, 0, _int_bits(A[:, :kp], "bf16"), _int_bits(B[:kp, :], "bf16"), "bf16",
+                             np.zeros((P, M, np_ + 1), np.float32))
+
+
 def test_activation_closed_forms_and_identities():
     x = np.linspace(-6, 6, 97)
     for kind in ("silu", "gelu_tanh"):
