@@ -463,6 +463,23 @@ def extras(pk, wl, torch, np, L):
     out["mlp_block_cfg4_silu_cfg3"] = {"ms": round(t_mlp, 4),
                                        "TFLOP/s": round((c3.flops + c4.flops) / (t_mlp * 1e-3) / 1e12, 1)}
 
+    # GEMM + reduce-scatter along the last dimension at the cfg3 shape (shard 8192 x 1024 instead of 1024 x 8192)
+    pc = pk.pk_gemm_rs_cols_plan(c3.P, c3.M, c3.N, c3.K, c3.dtype)
+    part_c = L["part"].view(c3.P, c3.M, c3.N // c3.P)              # same bytes, slots reinterpreted as [P][M][N/P]
+    outg_c = L["outgoing"].view(c3.P, c3.M, c3.N // c3.P)
+    out_c = torch.zeros((c3.M, c3.N // c3.P), dtype=torch.int16, device="cuda")
+    fin_c = torch.full((c3.P, pc.flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    fin_c[rank].zero_()
+    fout_c = torch.zeros_like(fin_c)
+    epc = [9 * 10 ** 6]
+
+    def rs_cols():
+        epc[0] += 1
+        pk.pk_gemm_rs_cols(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, part_c, outg_c, fin_c, fout_c,
+                           epc[0], out_c, pk.PHASE_ALL, L["status"])
+    t_cols = timeit(rs_cols)
+    out["gemm_rs_last_dim_cfg3_shape"] = {"ms": round(t_cols, 4), "TFLOP/s": round(c3.flops / (t_cols * 1e-3) / 1e12, 1)}
+
     # the paper's own element size for communicated tiles (s = 2): bf16 partial slots halve scatter and reduce traffic
     out["bf16_partial_slots"] = {}
     for name, c, A, B, sa, sb, part32, fin, fout, o in (("cfg3", c3, L["A3"], L["B3"], None, None, L["part"], L["flags_in"],

@@ -128,6 +128,31 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
+ * GEMM + reduce-scatter along the LAST dimension (paper appendix "Additional collective performance": reduce-scatter
+ * along the tensor dimension, whose pieces are not contiguous in memory).  As pk_gemm_rs, but rank q owns the column
+ * block N_q = [q*N/P, (q+1)*N/P) of every row:
+ *
+ *   columns N_q of own = A_local . B_local  -> outgoing[q] (q != rank), columns N_rank -> partials[rank]
+ *   out_shard = bf16( sum_{p<P} partials[p] )                     (M x N/P)
+ *
+ *   partials, outgoing  [P][M][N/P]   fp32 or bf16 (partial_dt)
+ *   flags_in, flags_out [P][flags_per_slot], flag grid = tiles of one M x N/P shard (pk_gemm_rs_cols_plan)
+ *   out_shard           M x N/P bf16
+ *
+ * Requirements: K % P == 0, N % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), (N/P) % 8 == 0 (bf16) or % 16 == 0
+ * (fp8); M is arbitrary; M and N/P need not be multiples of the tile (a tile never crosses a column block).  Everything
+ * else (phases, comm_cus, status, timeout_us, errors) as pk_gemm_rs.
+ */
+pk_status pk_gemm_rs_cols_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
+pk_status pk_gemm_rs_cols(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                          const void* A_local, const void* B_local,
+                          const float* scale_a, const float* scale_b,
+                          void* partials, void* outgoing,
+                          uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
+                          void* out_shard, uint32_t phases, int comm_cus, int partial_dt /* pk_partial_dtype */,
+                          uint32_t* status, uint64_t timeout_us, void* stream);
+
+/*
  * GEMM + all-reduce for rank `rank` (paper section 3.1.3, inter-SM overlapping: partial results are accumulated
  * in HBM, completion is signalled per tile, and the reduction is done once by dedicated workers; section 4.1,
  * figure "GEMM + AR").  Operands, `partials`, `outgoing`, `flags_in`, `flags_out` exactly as pk_gemm_rs.  There is

@@ -50,6 +50,10 @@ struct GemmArgs {
     int32_t group0;
     int32_t wg_per_group;     // 8 * ceil(grp_tile_rows * tiles_n / 8): tile slots of one group
     int32_t band;             // tile rows swept column-major inside a group (1 = plain row-major)
+    // scatter along the last dimension (reduce-scatter modes only; 0 = scatter along rows): destination rank from the
+    // tile column, tiles_n = P * tiles_n_shard, rows_per_shard = all rows, one row shard
+    int32_t cols_per_shard;   // N/P
+    int32_t tiles_n_shard;    // ceil(cols_per_shard / BN)
     int32_t rank;
     // reduce-scatter epilogue
     void* partials;           // [P][rows_per_shard][n], fp32 (EPI_RS) or bf16 (EPI_RS16)
@@ -191,7 +195,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     };
 
     // tile bookkeeping carried from one iteration to the next (the epilogue of a tile runs one iteration late)
-    int p_q = -1, p_tmi = 0, p_tc = 0, p_row0 = 0, p_row_end = 0, p_col0 = 0;
+    int p_q = -1, p_flag = 0, p_row0 = 0, p_row_end = 0, p_col0 = 0, p_col_end = 0;
     const int slots_total = g.wg_per_group * g.n_groups;
     const int G = g.grp_tile_rows * g.tiles_n;
     float scale = 1.f;
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             if (tid == 0) {
                 uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
                                                   : g.flags_out + (int64_t)p_q * g.flags_per_slot;
-                flag_publish(flags + (int64_t)p_tmi * g.tiles_n + p_tc, g.epoch);
+                flag_publish(flags + p_flag, g.epoch);
             }
         }
     };
@@ -231,7 +235,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                 break;
             }
         }
-        int q = 0, tmi = 0, tc = 0, row0 = 0, row_end = 0, col0 = 0;
+        int q = 0, tmi = 0, tc = 0, row0 = 0, row_end = 0, col0 = 0, col_end = 0, flag = 0;
         uint32_t a_voff[NA], b_voff[NB];           // per-lane byte offsets from the k-tile base pointers
         const char* a_base = g.A;                    // wave-uniform, advanced by one k-tile per issue
         const char* b_base = g.B;
@@ -251,6 +255,17 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             row0 = q * g.rows_per_shard + tmi * BM;
             row_end = (q + 1) * g.rows_per_shard;
             col0 = tc * BN;
+            col_end = g.n;
+            flag = tmi * g.tiles_n + tc;
+            if constexpr (EPI != EPI_AG) {
+                if (g.cols_per_shard > 0) {              // destination rank from the tile column (q was 0: one row shard)
+                    q = tc / g.tiles_n_shard;
+                    const int tci = tc - q * g.tiles_n_shard;
+                    col0 = q * g.cols_per_shard + tci * BN;
+                    col_end = (q + 1) * g.cols_per_shard;
+                    flag = tmi * g.tiles_n_shard + tci;
+                }
+            }
 
             // all-gather: wait until the chunk this tile reads has landed
             if constexpr (EPI == EPI_AG) {
@@ -350,11 +365,18 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             char* dst_base;
             int64_t dst_pitch;
             int dst_row0;                                    // global row -> row inside the destination
+            int dst_col0 = 0;                                // global column -> column inside the destination
             if constexpr (EPI != EPI_AG) {
                 dst_base = (p_q == g.rank) ? (char*)g.partials + (int64_t)g.rank * g.slot_elems * OUT_ELEM
                                            : (char*)g.outgoing + (int64_t)p_q * g.slot_elems * OUT_ELEM;
-                dst_pitch = (int64_t)g.n * OUT_ELEM;
-                dst_row0 = p_q * g.rows_per_shard;
+                if (g.cols_per_shard > 0) {
+                    dst_pitch = (int64_t)g.cols_per_shard * OUT_ELEM;
+                    dst_row0 = 0;
+                    dst_col0 = p_q * g.cols_per_shard;
+                } else {
+                    dst_pitch = (int64_t)g.n * OUT_ELEM;
+                    dst_row0 = p_q * g.rows_per_shard;
+                }
             } else {
                 dst_base = (char*)g.C;
                 dst_pitch = (int64_t)g.n * 2;
@@ -401,9 +423,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                         i32x4 val = *(PK_LDS i32x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16));
                         const int row = p_row0 + wm * (BM / WM) + ti * 32 + half * ROWS_PASS + rs;
                         const int col = col_w0 + ch * (16 / OUT_ELEM);
-                        if (row < p_row_end && col < g.n)
-{
-                            char* dp = dst_base + (int64_t)(row - dst_row0) * dst_pitch + (int64_t)col * OUT_ELEM;
+                        if (row < p_row_end && col < p_col_end) {
+                            char* dp = dst_base + (int64_t)(row - dst_row0) * dst_pitch + (int64_t)(col - dst_col0) * OUT_ELEM;
                             // reduce-scatter tiles are consumed by another kernel through a flag: write through
                             if constexpr (EPI != EPI_AG) store16_writethrough(dp, val);
                             else __builtin_nontemporal_store(val, (i32x4*)dp);
@@ -482,11 +503,11 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         }
 
         p_q = q;
-        p_tmi = tmi;
-        p_tc = tc;
+        p_flag = flag;
         p_row0 = row0;
         p_row_end = row_end;
         p_col0 = col0;
+        p_col_end = col_end;
     }
 
     // the last tile's stores: every wave waits for its write-through stores, then the flag is published

@@ -250,12 +250,15 @@ static int pick_band(int grp_tile_rows, int tiles_n, int run) {
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// rs: GEMM + reduce-scatter (K sharded) as opposed to all-gather + GEMM (N sharded); rs_cols: the reduce-scatter is along
+// the last dimension (then M need not divide by P, N must)
 static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, bool rs,
-                            int64_t* lm, int64_t* ln, int64_t* lk) {
+                            int64_t* lm, int64_t* ln, int64_t* lk, bool rs_cols = false) {
     if (dt != PK_BF16 && dt != PK_FP8_E4M3) return PK_ERR_DTYPE;
     if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || N < 1 || K < 1) return PK_ERR_SHAPE;
-    if (M % P) return PK_ERR_SHAPE;
+    if (M % P && !rs_cols) return PK_ERR_SHAPE;
     if (rs ? (K % P) : (N % P)) return PK_ERR_SHAPE;
+    if (rs_cols && (N % P || (N / P) % (dt == PK_FP8_E4M3 ? 16 : 8))) return PK_ERR_SHAPE;
     const int64_t m = M, n = rs ? N : N / P, k = rs ? K / P : K;
     const int kt = dt == PK_FP8_E4M3 ? 128 : 64, nv = dt == PK_FP8_E4M3 ? 16 : 8;
     if (k % kt || n % nv) return PK_ERR_SHAPE;
@@ -282,6 +285,27 @@ static pk_status make_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, 
     plan->flags_per_slot = (int64_t)plan->tiles_m * plan->tiles_n;
     plan->local_m = m;
     plan->local_n = n;
+    plan->local_k = k;
+    plan->ar_flags_per_slot = 0;
+    return PK_OK;
+}
+
+// Last-dimension scatter: the shard is M x N/P, flags cover tiles of that shard.
+static pk_status make_plan_cols(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    if (!plan) return PK_ERR_NULL;
+    int64_t m, n, k;
+    pk_status st = check_dims(P, M, N, K, dt, true, &m, &n, &k, true);
+    if (st != PK_OK) return st;
+    const int64_t ns = N / P;
+    const int64_t big = ceil_div(M, 256) * P * ceil_div(ns, 256);
+    const TileCfg tc = (M >= 256 && ns >= 256 && big >= 256) ? TileCfg{256, 256} : TileCfg{128, 128};
+    plan->tile_m = tc.bm;
+    plan->tile_n = tc.bn;
+    plan->tiles_m = (int32_t)ceil_div(M, tc.bm);
+    plan->tiles_n = (int32_t)ceil_div(ns, tc.bn);
+    plan->flags_per_slot = (int64_t)plan->tiles_m * plan->tiles_n;
+    plan->local_m = M;
+    plan->local_n = N;
     plan->local_k = k;
     plan->ar_flags_per_slot = 0;
     return PK_OK;
@@ -402,9 +426,9 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
                               const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
                               void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out,
                               uint32_t epoch, void* out_shard, const AllReduceOut* ar, uint32_t phases, int comm_cus,
-                              int partial_dt, uint32_t* status, uint64_t timeout_us, void* stream) {
+                              int partial_dt, bool cols, uint32_t* status, uint64_t timeout_us, void* stream) {
     pk_plan pl;
-    pk_status st = make_plan(P, M, N, K, dt, true, &pl);
+    pk_status st = cols ? make_plan_cols(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, true, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
     if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
@@ -422,7 +446,9 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         return PK_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     const TileCfg tc = {pl.tile_m, pl.tile_n};
-    const int64_t rows = M / P;
+    // one shard (slot): rows x cols.  Scatter along rows: M/P x N; along the last dimension: M x N/P
+    const int64_t rows = cols ? M : M / P;
+    const int64_t slot_cols = cols ? N / P : N;
 
     if (do_gemm) {
         GemmArgs a = {};
@@ -435,8 +461,10 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
         a.rows_per_shard = (int32_t)rows;
         a.tiles_m_shard = pl.tiles_m;
-        a.tiles_n = pl.tiles_n;
-        a.grp_tile_rows = P * pl.tiles_m;
+        a.tiles_n = cols ? P * pl.tiles_n : pl.tiles_n;
+        a.grp_tile_rows = cols ? pl.tiles_m : P * pl.tiles_m;
+        a.cols_per_shard = cols ? (int32_t)slot_cols : 0;
+        a.tiles_n_shard = cols ? pl.tiles_n : 0;
         a.n_groups = 1;
         a.group0 = 0;
         const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
@@ -447,7 +475,7 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.outgoing = outgoing;
         a.flags_in = flags_in;
         a.flags_out = flags_out;
-        a.slot_elems = rows * pl.local_n;
+        a.slot_elems = rows * slot_cols;
         a.flags_per_slot = pl.flags_per_slot;
         a.scale_a = scale_a;
         a.scale_b = scale_b;
@@ -465,13 +493,13 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         r.flags_in = flags_in;
         r.P = P;
         r.rows = (int32_t)rows;
-        r.n = (int32_t)pl.local_n;
+        r.n = (int32_t)slot_cols;
         r.tile_m = pl.tile_m;
         r.tile_n = pl.tile_n;
         r.tiles_n = pl.tiles_n;
         r.rows_sub = 8;                       // 8 rows x tile_n columns x P slots per workgroup
         r.sub = pl.tile_m / r.rows_sub;
-        r.slot_elems = rows * pl.local_n;
+        r.slot_elems = rows * slot_cols;
         r.flags_per_slot = pl.flags_per_slot;
         r.epoch = epoch;
         r.status = status;
@@ -535,7 +563,21 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      uint64_t timeout_us, void* stream) {
     if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
     return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, status, timeout_us, stream);
+                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, false, status, timeout_us, stream);
+}
+
+pk_status pk_gemm_rs_cols_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    return make_plan_cols(P, M, N, K, dt, plan);
+}
+
+pk_status pk_gemm_rs_cols(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                          const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
+                          void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
+                          void* out_shard, uint32_t phases, int comm_cus, int partial_dt, uint32_t* status,
+                          uint64_t timeout_us, void* stream) {
+    if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
+    return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
+                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, true, status, timeout_us, stream);
 }
 
 pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -564,7 +606,7 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         // the reduce phase writes rows R_rank of out_full
         uint16_t* own_rows = (uint16_t*)out_full + (int64_t)rank * (M / P) * N;
         st = gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, partial_dt, status, timeout_us, stream);
+                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, partial_dt, false, status, timeout_us, stream);
         if (st != PK_OK) return st;
     }
     if (phases & PK_PHASE_WAIT) {

@@ -25,7 +25,8 @@ DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
 
 EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_ag_gemm_plan", "pk_ag_gemm",
            "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy",
-           "pk_gemm_ar_plan", "pk_gemm_ar", "pk_emu_deliver_chunks_dma"]
+           "pk_gemm_ar_plan", "pk_gemm_ar", "pk_emu_deliver_chunks_dma",
+           "pk_gemm_rs_cols_plan", "pk_gemm_rs_cols"]
 
 
 class Plan(ctypes.Structure):
@@ -57,7 +58,7 @@ def lib():
         L.pk_version.restype = ctypes.c_int
         L.pk_status_str.restype = ctypes.c_char_p
         L.pk_status_str.argtypes = [i32]
-        for f in (L.pk_gemm_rs_plan, L.pk_ag_gemm_plan, L.pk_gemm_ar_plan):
+        for f in (L.pk_gemm_rs_plan, L.pk_ag_gemm_plan, L.pk_gemm_ar_plan, L.pk_gemm_rs_cols_plan):
             f.restype = i32
             f.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.pk_gemm_rs.restype = i32
@@ -70,6 +71,8 @@ def lib():
         L.pk_emu_deliver_partials.argtypes = [i32, i64, i64, i32, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp]
         L.pk_probe_mfma.restype = i32
         L.pk_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pk_gemm_rs_cols.restype = i32
+        L.pk_gemm_rs_cols.argtypes = L.pk_gemm_rs.argtypes
         L.pk_gemm_ar.restype = i32
         L.pk_gemm_ar.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, i32,
                                  i32, vp, u64, vp]
@@ -139,6 +142,21 @@ def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, part
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
                             _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), _ptr(status), timeout_us,
                             _stream(stream)), "pk_gemm_rs")
+
+
+def pk_gemm_rs_cols_plan(P, M, N, K, dtype):
+    p = Plan()
+    _check(lib().pk_gemm_rs_cols_plan(P, M, N, K, _dt(dtype), ctypes.byref(p)), "pk_gemm_rs_cols_plan")
+    return p
+
+
+def pk_gemm_rs_cols(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing,
+                    flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None, comm_cus=0,
+                    partial_dtype="f32"):
+    _check(lib().pk_gemm_rs_cols(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a),
+                                 _ptr(scale_b), _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
+                                 _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), _ptr(status), timeout_us,
+                                 _stream(stream)), "pk_gemm_rs_cols")
 
 
 def pk_gemm_ar_plan(P, M, N, K, dtype):

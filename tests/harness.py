@@ -60,12 +60,13 @@ def deliver_slots(P, M, N, tile_m, tile_n, staging, part, flags, epoch, order, g
 
 def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
-                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0, partial_dtype="f32"):
+                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0, partial_dtype="f32", cols=False):
     """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
 
     partition = (compute_stream, comm_stream) handles from pk_partition_create: the op then runs on the first and
     the emulated peers on the second.
     partial_dtype = "bf16": `partials` holds uint16 bit patterns; outgoing / partials_after come back as uint16.
+    cols = True: pk_gemm_rs_cols (scatter along the last dimension): slots and the output are M x N/P.
 
     deliver = "pre": peer slots and their flags are in place before the call.
     deliver = "emu": peer slots start as NaN; pk_emu_deliver_partials copies them in on a second stream,
@@ -74,15 +75,18 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
     Returns dict with out_bits (uint16), outgoing, partials_after, flags_out, flags_in, status, plan.
     lazy=True leaves the two big fp32 arrays on the device (keys outgoing_t, partials_t) instead.
     """
-    plan = pk.pk_gemm_rs_plan(P, M, N, K, dtype)
-    mp = M // P
+    plan = (pk.pk_gemm_rs_cols_plan if cols else pk.pk_gemm_rs_plan)(P, M, N, K, dtype)
+    op = pk.pk_gemm_rs_cols if cols else pk.pk_gemm_rs
+    # one shard is mp rows x ncols columns; the emulator sees [P][mp][ncols] slots of a (P*mp) x ncols problem
+    mp = M if cols else M // P
+    ncols = N // P if cols else N
     fps = plan.flags_per_slot
     A = elem_view(A_bits, dtype)
     B = elem_view(B_bits, dtype)
     sa, sb = scale_t(scale_a), scale_t(scale_b)
-    out = torch.full((mp, N), -1, dtype=torch.int16, device="cuda")
+    out = torch.full((mp, ncols), -1, dtype=torch.int16, device="cuda")
     s16 = partial_dtype == "bf16"
-    outgoing = slot_poison(P, mp, N, s16)
+    outgoing = slot_poison(P, mp, ncols, s16)
     flags_in = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     status = torch.zeros(4, dtype=torch.int32, device="cuda")
@@ -92,7 +96,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
     main = torch.cuda.current_stream() if partition is None else torch.cuda.ExternalStream(partition[0])
     if deliver == "pre":
         part = slot_upload(partials, s16)
-        part[rank].copy_(slot_poison(1, mp, N, s16)[0])
+        part[rank].copy_(slot_poison(1, mp, ncols, s16)[0])
         for q in peers:
             flags_in[q].fill_(epoch)
         if withhold is not None:
@@ -100,13 +104,14 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
         torch.cuda.synchronize()
     else:
         staging = slot_upload(partials, s16)
-        part = slot_poison(P, mp, N, s16)
+        part = slot_poison(P, mp, ncols, s16)
         torch.cuda.synchronize()
         side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
-        deliver_slots(P, M, N, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us, side, n_wg, s16)
-    pk.pk_gemm_rs(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
-                  flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main,
-                  comm_cus=comm_cus, partial_dtype=partial_dtype)
+        deliver_slots(P, P * mp, ncols, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us, side,
+                      n_wg, s16)
+    op(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
+       flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main,
+       comm_cus=comm_cus, partial_dtype=partial_dtype)
     torch.cuda.synchronize()
     res = {"out_bits": bits_of(out), "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
            "status": status.cpu().numpy(), "plan": plan}

@@ -171,3 +171,26 @@ def test_binding_raises_pk_error():
     with pytest.raises(pk.PkError) as e:
         pk.pk_gemm_rs_plan(3, 256, 256, 512, "bf16")
     assert e.value.code == pk.ERR_SHAPE
+
+
+def test_gemm_rs_cols_plan_and_argument_errors_launch_nothing():
+    p = pk.pk_gemm_rs_cols_plan(8, 8192, 8192, 28672, "bf16")
+    assert (p.tile_m, p.tile_n, p.tiles_m, p.tiles_n, p.flags_per_slot) == (256, 256, 32, 4, 128)
+    assert (p.local_m, p.local_n, p.local_k) == (8192, 8192, 3584)
+    p = pk.pk_gemm_rs_cols_plan(4, 136, 4 * 264, 1024, "bf16")             # M not a multiple of P is fine here
+    assert (p.tile_m, p.tiles_m, p.tiles_n) == (128, 2, 3)
+    plan = pk.Plan()
+    L = pk.lib()
+    assert L.pk_gemm_rs_cols_plan(4, 136, 4 * 260, 1024, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE     # (N/P) % 8
+    assert L.pk_gemm_rs_cols_plan(4, 136, 1058, 1024, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE         # N % P
+    assert L.pk_gemm_rs_cols_plan(4, 136, 1056, 1000, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE         # K/P % 64
+    assert L.pk_gemm_rs_cols_plan(4, 136, 1056, 1024, pk.BF16, None) == pk.ERR_NULL
+
+    def rs(rank=0, part=0x3000, phases=3, pdt=0, out=0x7000):
+        return L.pk_gemm_rs_cols(2, rank, 300, 512, 512, pk.BF16, 0x1000, 0x2000, None, None, part, 0x4000, 0x5000, 0x6000, 1,
+                                 out, phases, 0, pdt, 0x8000, 0, None)
+    assert rs(rank=2) == pk.ERR_RANK
+    assert rs(part=None) == pk.ERR_NULL
+    assert rs(phases=0) == pk.ERR_ARG
+    assert rs(pdt=7) == pk.ERR_DTYPE
+    assert rs(out=0x7001) == pk.ERR_ALIGN
