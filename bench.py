@@ -383,6 +383,24 @@ def extras(pk, wl, torch, np, L):
     out["ag_gemm_live_copy_engine"] = {"ms_live_ring_arrival": round(t_dma, 4), "ms_copies_alone": round(t_dma_alone, 4),
                                        "TFLOP/s_live": round(c4.flops / (t_dma * 1e-3) / 1e12, 1)}
 
+    # all-gather along the last dimension of A (column chunks, strided copies) at the cfg4 shape
+    def ag_k_pre():
+        pk.pk_ag_gemm_k(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, L["chunk_flags"], 1, L["C4"],
+                        L["status"])
+    t_k_pre = timeit(ag_k_pre)
+
+    def ag_k_live():
+        epd[0] += 1
+        done2.record(stream)
+        side2.wait_event(done2)
+        pk.pk_emu_deliver_kchunks_dma(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_dma, epd[0], order, stream=side2)
+        pk.pk_ag_gemm_k(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_dma, epd[0], L["C4"],
+                        L["status"])
+        stream.wait_stream(side2)
+    t_k_live = timeit(ag_k_live)
+    out["ag_gemm_last_dim_cfg4_shape"] = {"ms_prelanded": round(t_k_pre, 4), "ms_live_ring_arrival_strided_copies": round(t_k_live, 4),
+                                          "TFLOP/s_prelanded": round(c4.flops / (t_k_pre * 1e-3) / 1e12, 1)}
+
     out.update(live(32))
     out["comm_cus_sweep"] = {}
     for cc in (16, 64):

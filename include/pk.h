@@ -215,6 +215,23 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
+ * All-gather along the LAST dimension of A + GEMM (paper appendix "Additional collective performance": all-gather along
+ * the tensor dimension, whose pieces are not contiguous in memory).  As pk_ag_gemm, but chunk q of A_gathered is the
+ * column block K_q = [q*K/P, (q+1)*K/P) of every row (M pieces of K/P elements), valid once chunk_flags[q] has reached
+ * `epoch` (chunk `rank` at the call).  Every output tile needs every chunk: the k-loop runs chunk by chunk in ring order
+ * from the own one, and the first tile of a workgroup that reaches a chunk waits for its flag.
+ * Requirements: N % P == 0, K % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), (N/P) % 8 == 0 (bf16) or % 16 == 0
+ * (fp8); M is arbitrary.  On a timeout the workgroup that waited stops: its current and remaining tiles stay unwritten.
+ */
+pk_status pk_ag_gemm_k_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
+pk_status pk_ag_gemm_k(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                       const void* A_gathered, const void* B_local,
+                       const float* scale_a, const float* scale_b,
+                       const uint32_t* chunk_flags, uint32_t epoch,
+                       void* C_local, int comm_cus, int activation /* pk_activation */,
+                       uint32_t* status, uint64_t timeout_us, void* stream);
+
+/*
  * Peer emulation (tests and benchmarks only; stands in for what other ranks would push over the fabric).
  *
  * pk_emu_deliver_chunks: for i = 0..n_order-1, copy chunk q = order[i] (M/P x K elements of `elem_bytes`
@@ -243,6 +260,12 @@ pk_status pk_emu_deliver_chunks_dma(int P, int64_t M, int64_t K, int elem_bytes,
                                     const void* staging, void* A_gathered,
                                     uint32_t* chunk_flags, uint32_t epoch,
                                     const int* order /* host */, int n_order, void* stream);
+/* Column chunks for pk_ag_gemm_k, moved the same way: one strided (2-D) device-to-device copy per chunk, M pieces of
+ * K/P elements, then the chunk's flag by a stream memory operation. */
+pk_status pk_emu_deliver_kchunks_dma(int P, int64_t M, int64_t K, int elem_bytes,
+                                     const void* staging, void* A_gathered,
+                                     uint32_t* chunk_flags, uint32_t epoch,
+                                     const int* order /* host */, int n_order, void* stream);
 pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int tile_n,
                                   const float* staging, float* partials,
                                   uint32_t* flags_in, uint32_t epoch,

@@ -228,6 +228,12 @@ def activation(x, kind):
     raise ValueError(f"unknown activation {kind!r}")
 
 
+def gather_kchunks(chunks):
+    """A gathered along its LAST dimension (appendix "Additional collective performance": all-gather along the
+    tensor dimension): chunk q = columns K_q = [q*K/P, (q+1)*K/P) of every row.  The GEMM that follows is ag_gemm."""
+    return np.concatenate([np.asarray(c) for c in chunks], axis=1)
+
+
 def ag_gemm(P, rank, a_gathered_bits, b_local_bits, dtype,
             scale_a=None, scale_b=None, rows=None, act="none"):
     """One rank's all-gather + GEMM: C[:, N_rank] = act( A . B[:, N_rank] ).

@@ -31,7 +31,8 @@
 
 namespace pk {
 
-enum { EPI_RS = 0, EPI_AG = 1, EPI_RS16 = 2 };   // reduce-scatter with fp32 slots, all-gather, reduce-scatter with bf16 slots
+// reduce-scatter with fp32 slots; all-gather of row chunks; reduce-scatter with bf16 slots; all-gather of column (K) chunks
+enum { EPI_RS = 0, EPI_AG = 1, EPI_RS16 = 2, EPI_AGK = 3 };
 
 struct GemmArgs {
     const char* A;            // local first operand, row-major
@@ -65,6 +66,7 @@ struct GemmArgs {
     // all-gather epilogue
     uint16_t* C;              // (P*rows_per_shard) x n bf16
     const uint32_t* chunk_flags;
+    int32_t k_chunks;         // EPI_AGK: A arrives in this many column blocks of K/k_chunks (chunk q from rank q)
     int32_t act;              // pk_activation applied to the accumulator before the bf16 rounding (all-gather mode)
     const float* scale_a;     // fp8 only
     const float* scale_b;
@@ -86,6 +88,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     PK_LDS char* lds = (PK_LDS char*)smem_generic;
 
+    constexpr bool IS_RS = EPI == EPI_RS || EPI == EPI_RS16;
     constexpr int NW = WM * WN;                          // waves per workgroup
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 accumulators per wave: TM x TN
     constexpr int A_BYTES = BM * KB, B_BYTES = BN * KB, STAGE = A_BYTES + B_BYTES;
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     };
 
     auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
-        if constexpr (EPI != EPI_AG) {
+        if constexpr (IS_RS) {
             if (tid == 0) {
                 uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
                                                   : g.flags_out + (int64_t)p_q * g.flags_per_slot;
@@ -220,6 +223,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         }
     };
 
+    uint64_t seen_chunks = 0;   // EPI_AGK: column chunks of A this workgroup has already waited for
     int v = blockIdx.x;
     for (;;) {
         // ---- which tile (paper listing: interpret_task) ----
@@ -240,6 +244,13 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         const char* a_base = g.A;                    // wave-uniform, advanced by one k-tile per issue
         const char* b_base = g.B;
         const int64_t b_step = (int64_t)B_ROWS * g.ldb;
+        // k-tiles handled between two pipeline fills: all of them, or one column chunk of A at a time (EPI_AGK, own
+        // chunk first)
+        const int seg_ktiles = (EPI == EPI_AGK) ? g.ktiles / g.k_chunks : g.ktiles;
+        if constexpr (EPI == EPI_AGK) {
+            a_base += (int64_t)g.rank * seg_ktiles * KB;
+            b_base += (int64_t)g.rank * seg_ktiles * b_step;
+        }
         if (have) {
             const int BAND = g.band > 0 ? g.band : 1;
             const int band = t / (BAND * g.tiles_n);
@@ -257,7 +268,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             col0 = tc * BN;
             col_end = g.n;
             flag = tmi * g.tiles_n + tc;
-            if constexpr (EPI != EPI_AG) {
+            if constexpr (IS_RS) {
                 if (g.cols_per_shard > 0) {              // destination rank from the tile column (q was 0: one row shard)
                     q = tc / g.tiles_n_shard;
                     const int tci = tc - q * g.tiles_n_shard;
@@ -344,7 +355,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         if (have) {
 #pragma unroll
             for (int s = 0; s < NS; ++s)
-                if (s < g.ktiles) issue_loads(s);
+                if (s < seg_ktiles) issue_loads(s);
         }
 
         // ---- epilogue of the previous tile (the storer), under the latency of the loads just issued ----
@@ -366,7 +377,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             int64_t dst_pitch;
             int dst_row0;                                    // global row -> row inside the destination
             int dst_col0 = 0;                                // global column -> column inside the destination
-            if constexpr (EPI != EPI_AG) {
+            if constexpr (IS_RS) {
                 dst_base = (p_q == g.rank) ? (char*)g.partials + (int64_t)g.rank * g.slot_elems * OUT_ELEM
                                            : (char*)g.outgoing + (int64_t)p_q * g.slot_elems * OUT_ELEM;
                 if (g.cols_per_shard > 0) {
@@ -404,7 +415,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                                     const int ch = colw >> 3;                  // 16-byte chunk (8 bf16)
                                     float x0 = acc[ti][tj][4 * b] * scale, x1 = acc[ti][tj][4 * b + 1] * scale,
                                           x2 = acc[ti][tj][4 * b + 2] * scale, x3 = acc[ti][tj][4 * b + 3] * scale;
-                                    if constexpr (EPI == EPI_AG) {
+                                    if constexpr (!IS_RS) {
                                         x0 = activate(x0);
                                         x1 = activate(x1);
                                         x2 = activate(x2);
@@ -426,7 +437,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                         if (row < p_row_end && col < p_col_end) {
                             char* dp = dst_base + (int64_t)(row - dst_row0) * dst_pitch + (int64_t)(col - dst_col0) * OUT_ELEM;
                             // reduce-scatter tiles are consumed by another kernel through a flag: write through
-                            if constexpr (EPI != EPI_AG) store16_writethrough(dp, val);
+                            if constexpr (IS_RS) store16_writethrough(dp, val);
                             else __builtin_nontemporal_store(val, (i32x4*)dp);
                         }
                     }
@@ -449,7 +460,6 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 
         // ---- main loop ----
         frag_t af0[TM], bf0[TN], af1[TM], bf1[TN];
-        load_frags(lds, 0, af0, bf0);
         // One k-tile: KS-1 pipelined k-steps, the barrier, then the last k-step, under which the loads of
         // k-tile kt+NS (LOADS) and the first fragments of k-tile kt+1 (NEXT) are issued.  At the barrier every
         // wave has finished reading k-tile kt's stage, so it can be refilled, and k-tile kt+1 has landed: in the
@@ -495,11 +505,44 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             __syncthreads();
             kstep(af1, bf1, af0, bf0, nx, 0, next_c, sidx, loads_c);
         };
-        {
+        // the k-tiles of one pipeline fill: the first NS are in flight or landed, stage 0 holds the first
+        auto run_ktiles = [&](int nkt) {
+            load_frags(lds, 0, af0, bf0);
             int kt = 0;
-            for (; kt + NS < g.ktiles; ++kt) ktile(kt, std::true_type{}, std::true_type{});
-            for (; kt + 1 < g.ktiles; ++kt) ktile(kt, std::false_type{}, std::true_type{});
+            for (; kt + NS < nkt; ++kt) ktile(kt, std::true_type{}, std::true_type{});
+            for (; kt + 1 < nkt; ++kt) ktile(kt, std::false_type{}, std::true_type{});
             ktile(kt, std::false_type{}, std::false_type{});
+        };
+        run_ktiles(seg_ktiles);
+        if constexpr (EPI == EPI_AGK) {
+            // the other column chunks of A, in ring order from the own one; the first tile that touches a chunk waits for
+            // its flag (paper appendix C `wait`), later tiles of this workgroup know it has landed
+            for (int sgm = 1; sgm < g.k_chunks; ++sgm) {
+                int c = g.rank + sgm;
+                if (c >= g.k_chunks) c -= g.k_chunks;
+                if (!((seen_chunks >> c) & 1)) {
+                    PK_LDS int* verdict = (PK_LDS int*)(lds + EPI_OFF);
+                    if (tid == 0) {
+                        const int late = flag_wait(g.chunk_flags + c, g.epoch, g.timeout_ticks) ? 0 : 1;
+                        if (late) report_timeout(g.status, (uint32_t)c, 1u);
+                        *verdict = late;
+                    }
+                    __syncthreads();
+                    const int late_all = *verdict;
+                    __syncthreads();
+                    if (late_all) return;                 // drain: this tile and the rest of this workgroup's stay untouched
+                    acquire_agent();
+                    seen_chunks |= 1ull << c;
+                }
+                a_base = g.A + (int64_t)c * seg_ktiles * KB;
+                b_base = g.B + (int64_t)c * seg_ktiles * b_step;
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+                    if (s < seg_ktiles) issue_loads(s);
+                __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
+                __syncthreads();
+                run_ktiles(seg_ktiles);
+            }
         }
 
         p_q = q;
@@ -511,7 +554,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     }
 
     // the last tile's stores: every wave waits for its write-through stores, then the flag is published
-    if constexpr (EPI != EPI_AG) {
+    if constexpr (IS_RS) {
         if (p_q >= 0) {
             __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
             __syncthreads();

@@ -251,17 +251,18 @@ static int pick_band(int grp_tile_rows, int tiles_n, int run) {
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 // rs: GEMM + reduce-scatter (K sharded) as opposed to all-gather + GEMM (N sharded); rs_cols: the reduce-scatter is along
-// the last dimension (then M need not divide by P, N must)
+// the last dimension (then M need not divide by P, N must); ag_k: the all-gather is along the last dimension of A (K)
 static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, bool rs,
-                            int64_t* lm, int64_t* ln, int64_t* lk, bool rs_cols = false) {
+                            int64_t* lm, int64_t* ln, int64_t* lk, bool rs_cols = false, bool ag_k = false) {
     if (dt != PK_BF16 && dt != PK_FP8_E4M3) return PK_ERR_DTYPE;
     if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || N < 1 || K < 1) return PK_ERR_SHAPE;
-    if (M % P && !rs_cols) return PK_ERR_SHAPE;
+    if (M % P && !rs_cols && !ag_k) return PK_ERR_SHAPE;
     if (rs ? (K % P) : (N % P)) return PK_ERR_SHAPE;
     if (rs_cols && (N % P || (N / P) % (dt == PK_FP8_E4M3 ? 16 : 8))) return PK_ERR_SHAPE;
     const int64_t m = M, n = rs ? N : N / P, k = rs ? K / P : K;
     const int kt = dt == PK_FP8_E4M3 ? 128 : 64, nv = dt == PK_FP8_E4M3 ? 16 : 8;
     if (k % kt || n % nv) return PK_ERR_SHAPE;
+    if (ag_k && (K % P || (K / P) % kt)) return PK_ERR_SHAPE;   // A arrives in column chunks of whole k-tiles
     if (m > (1 << 30) || n > (1 << 30) || k > (1 << 30)) return PK_ERR_SHAPE;
     // the kernels address each operand, and the fp32 partial slots, with 32-bit byte offsets from their base
     if (m * k * 2 >= ((int64_t)1 << 32) || k * n * 2 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
@@ -529,6 +530,85 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     return PK_OK;
 }
 
+static pk_status make_plan_ag_k(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    if (!plan) return PK_ERR_NULL;
+    int64_t m, n, k;
+    pk_status st = check_dims(P, M, N, K, dt, false, &m, &n, &k, false, true);
+    if (st != PK_OK) return st;
+    const TileCfg tc = pick_tile(1, M, n);
+    plan->tile_m = tc.bm;
+    plan->tile_n = tc.bn;
+    plan->tiles_m = (int32_t)ceil_div(M, tc.bm);
+    plan->tiles_n = (int32_t)ceil_div(n, tc.bn);
+    plan->flags_per_slot = (int64_t)plan->tiles_m * plan->tiles_n;
+    plan->local_m = m;
+    plan->local_n = n;
+    plan->local_k = k;
+    plan->ar_flags_per_slot = 0;
+    return PK_OK;
+}
+
+static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                              const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
+                              const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
+                              bool k_chunks, uint32_t* status, uint64_t timeout_us, void* stream) {
+    pk_plan pl;
+    pk_status st = k_chunks ? make_plan_ag_k(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, false, &pl);
+    if (st != PK_OK) return st;
+    if (rank < 0 || rank >= P) return PK_ERR_RANK;
+    if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
+    if (activation < PK_ACT_NONE || activation > PK_ACT_SILU) return PK_ERR_ARG;
+    const bool fp8 = dt == PK_FP8_E4M3;
+    if (!A_gathered || !B_local || !C_local || !status) return PK_ERR_NULL;
+    if (P > 1 && !chunk_flags) return PK_ERR_NULL;
+    if (fp8 && (!scale_a || !scale_b)) return PK_ERR_DTYPE;
+    if (!aligned16(A_gathered) || !aligned16(B_local) || !aligned16(C_local)) return PK_ERR_ALIGN;
+    const TileCfg tc = {pl.tile_m, pl.tile_n};
+    const int elem = fp8 ? 1 : 2;
+    GemmArgs a = {};
+    a.A = (const char*)A_gathered;
+    a.B = (const char*)B_local;
+    a.lda = pl.local_k * elem;
+    a.ldb = pl.local_n * elem;
+    a.n = (int32_t)pl.local_n;
+    a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
+    // row chunks: one scheduling group per chunk, visited from the own one; column chunks: every tile needs every chunk
+    a.rows_per_shard = (int32_t)(k_chunks ? M : M / P);
+    a.tiles_m_shard = pl.tiles_m;
+    a.tiles_n = pl.tiles_n;
+    a.grp_tile_rows = pl.tiles_m;
+    a.n_groups = k_chunks ? 1 : P;
+    a.group0 = k_chunks ? 0 : rank;
+    a.k_chunks = k_chunks ? P : 0;
+    a.act = activation;
+    const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
+    a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
+    a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);
+    a.rank = rank;
+    a.C = (uint16_t*)C_local;
+    a.chunk_flags = chunk_flags;
+    a.scale_a = scale_a;
+    a.scale_b = scale_b;
+    a.epoch = epoch;
+    a.status = status;
+    a.timeout_ticks = timeout_ticks(timeout_us);
+    return k_chunks ? dispatch_gemm<EPI_AGK>(a, a.wg_per_group, comm_cus, tc, fp8, (hipStream_t)stream)
+                    : dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, (hipStream_t)stream);
+}
+
+static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
+    if (n_order < 0 || n_order > PK_EMU_MAX_ORDER) return PK_ERR_ARG;
+    if (n_order > 0 && !order) return PK_ERR_NULL;
+    o->n = n_order;
+    for (int i = 0; i < n_order; ++i) {
+        if (order[i] < 0 || order[i] >= P) return PK_ERR_ARG;
+        for (int j = 0; j < i; ++j)
+            if (order[j] == order[i]) return PK_ERR_ARG;
+        o->q[i] = order[i];
+    }
+    return PK_OK;
+}
+
 extern "C" {
 
 int pk_version(void) { return 1; }
@@ -622,56 +702,39 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
                      uint32_t* status, uint64_t timeout_us, void* stream) {
-    pk_plan pl;
-    pk_status st = make_plan(P, M, N, K, dt, false, &pl);
-    if (st != PK_OK) return st;
-    if (rank < 0 || rank >= P) return PK_ERR_RANK;
-    if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
-    if (activation < PK_ACT_NONE || activation > PK_ACT_SILU) return PK_ERR_ARG;
-    const bool fp8 = dt == PK_FP8_E4M3;
-    if (!A_gathered || !B_local || !C_local || !status) return PK_ERR_NULL;
-    if (P > 1 && !chunk_flags) return PK_ERR_NULL;
-    if (fp8 && (!scale_a || !scale_b)) return PK_ERR_DTYPE;
-    if (!aligned16(A_gathered) || !aligned16(B_local) || !aligned16(C_local)) return PK_ERR_ALIGN;
-    const TileCfg tc = {pl.tile_m, pl.tile_n};
-    const int elem = fp8 ? 1 : 2;
-    GemmArgs a = {};
-    a.A = (const char*)A_gathered;
-    a.B = (const char*)B_local;
-    a.lda = pl.local_k * elem;
-    a.ldb = pl.local_n * elem;
-    a.n = (int32_t)pl.local_n;
-    a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
-    a.rows_per_shard = (int32_t)(M / P);
-    a.tiles_m_shard = pl.tiles_m;
-    a.tiles_n = pl.tiles_n;
-    a.grp_tile_rows = pl.tiles_m;
-    a.n_groups = P;
-    a.group0 = rank;
-    a.act = activation;
-    const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
-    a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
-    a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);
-    a.rank = rank;
-    a.C = (uint16_t*)C_local;
-    a.chunk_flags = chunk_flags;
-    a.scale_a = scale_a;
-    a.scale_b = scale_b;
-    a.epoch = epoch;
-    a.status = status;
-    a.timeout_ticks = timeout_ticks(timeout_us);
-    return dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, (hipStream_t)stream);
+    return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
+                        activation, false, status, timeout_us, stream);
 }
 
-static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
-    if (n_order < 0 || n_order > PK_EMU_MAX_ORDER) return PK_ERR_ARG;
-    if (n_order > 0 && !order) return PK_ERR_NULL;
-    o->n = n_order;
-    for (int i = 0; i < n_order; ++i) {
-        if (order[i] < 0 || order[i] >= P) return PK_ERR_ARG;
-        for (int j = 0; j < i; ++j)
-            if (order[j] == order[i]) return PK_ERR_ARG;
-        o->q[i] = order[i];
+pk_status pk_ag_gemm_k_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
+    return make_plan_ag_k(P, M, N, K, dt, plan);
+}
+
+pk_status pk_ag_gemm_k(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                       const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
+                       const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
+                       uint32_t* status, uint64_t timeout_us, void* stream) {
+    return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
+                        activation, true, status, timeout_us, stream);
+}
+
+pk_status pk_emu_deliver_kchunks_dma(int P, int64_t M, int64_t K, int elem_bytes, const void* staging, void* A_gathered,
+                                     uint32_t* chunk_flags, uint32_t epoch, const int* order, int n_order, void* stream) {
+    if (P < 1 || P > PK_EMU_MAX_ORDER || M < 1 || K < 1 || K % P) return PK_ERR_SHAPE;
+    if (elem_bytes != 1 && elem_bytes != 2) return PK_ERR_DTYPE;
+    if (!staging || !A_gathered || !chunk_flags) return PK_ERR_NULL;
+    const size_t pitch = (size_t)K * elem_bytes, width = (size_t)(K / P) * elem_bytes;
+    EmuOrder o;
+    pk_status st = make_order(order, n_order, P, &o);
+    if (st != PK_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    for (int i = 0; i < o.n; ++i) {
+        const size_t off = (size_t)o.q[i] * width;
+        // M pieces of K/P elements, one per row: the strided layout of a gather along the last dimension
+        if (hipMemcpy2DAsync((char*)A_gathered + off, pitch, (const char*)staging + off, pitch, width, (size_t)M,
+                             hipMemcpyDeviceToDevice, s) != hipSuccess)
+            return PK_ERR_HIP;
+        if (hipStreamWriteValue32(s, chunk_flags + o.q[i], epoch, 0) != hipSuccess) return PK_ERR_HIP;
     }
     return PK_OK;
 }

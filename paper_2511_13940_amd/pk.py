@@ -26,7 +26,8 @@ DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
 EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_ag_gemm_plan", "pk_ag_gemm",
            "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy",
            "pk_gemm_ar_plan", "pk_gemm_ar", "pk_emu_deliver_chunks_dma",
-           "pk_gemm_rs_cols_plan", "pk_gemm_rs_cols"]
+           "pk_gemm_rs_cols_plan", "pk_gemm_rs_cols", "pk_ag_gemm_k_plan", "pk_ag_gemm_k",
+           "pk_emu_deliver_kchunks_dma"]
 
 
 class Plan(ctypes.Structure):
@@ -58,7 +59,7 @@ def lib():
         L.pk_version.restype = ctypes.c_int
         L.pk_status_str.restype = ctypes.c_char_p
         L.pk_status_str.argtypes = [i32]
-        for f in (L.pk_gemm_rs_plan, L.pk_ag_gemm_plan, L.pk_gemm_ar_plan, L.pk_gemm_rs_cols_plan):
+        for f in (L.pk_gemm_rs_plan, L.pk_ag_gemm_plan, L.pk_gemm_ar_plan, L.pk_gemm_rs_cols_plan, L.pk_ag_gemm_k_plan):
             f.restype = i32
             f.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.pk_gemm_rs.restype = i32
@@ -76,6 +77,10 @@ def lib():
         L.pk_gemm_ar.restype = i32
         L.pk_gemm_ar.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, i32,
                                  i32, vp, u64, vp]
+        L.pk_ag_gemm_k.restype = i32
+        L.pk_ag_gemm_k.argtypes = L.pk_ag_gemm.argtypes
+        L.pk_emu_deliver_kchunks_dma.restype = i32
+        L.pk_emu_deliver_kchunks_dma.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, vp]
         L.pk_emu_deliver_chunks_dma.restype = i32
         L.pk_emu_deliver_chunks_dma.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, vp]
         L.pk_partition_create.restype = i32
@@ -182,6 +187,20 @@ def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, c
                             timeout_us, _stream(stream)), "pk_ag_gemm")
 
 
+def pk_ag_gemm_k_plan(P, M, N, K, dtype):
+    p = Plan()
+    _check(lib().pk_ag_gemm_k_plan(P, M, N, K, _dt(dtype), ctypes.byref(p)), "pk_ag_gemm_k_plan")
+    return p
+
+
+def pk_ag_gemm_k(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
+                 C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none"):
+    _check(lib().pk_ag_gemm_k(P, rank, M, N, K, _dt(dtype), _ptr(A_gathered), _ptr(B_local), _ptr(scale_a),
+                              _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus,
+                              ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(status),
+                              timeout_us, _stream(stream)), "pk_ag_gemm_k")
+
+
 def _order(order):
     arr = (ctypes.c_int * max(1, len(order)))(*order)
     return arr, len(order)
@@ -199,6 +218,12 @@ def pk_emu_deliver_chunks_dma(P, M, K, elem_bytes, staging, A_gathered, chunk_fl
     arr, n = _order(order)
     _check(lib().pk_emu_deliver_chunks_dma(P, M, K, elem_bytes, _ptr(staging), _ptr(A_gathered), _ptr(chunk_flags), epoch,
                                            arr, n, _stream(stream)), "pk_emu_deliver_chunks_dma")
+
+
+def pk_emu_deliver_kchunks_dma(P, M, K, elem_bytes, staging, A_gathered, chunk_flags, epoch, order, stream=None):
+    arr, n = _order(order)
+    _check(lib().pk_emu_deliver_kchunks_dma(P, M, K, elem_bytes, _ptr(staging), _ptr(A_gathered), _ptr(chunk_flags), epoch,
+                                            arr, n, _stream(stream)), "pk_emu_deliver_kchunks_dma")
 
 
 def pk_emu_deliver_partials(P, M, N, tile_m, tile_n, staging, partials, flags_in, epoch, order, gap_us,

@@ -233,3 +233,47 @@ def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, sc
     return {"full_bits": bits_of(full), "bcast_bits": bits_of(bcast), "ar_in": ar_in.cpu().numpy(),
             "ar_out": ar_out.cpu().numpy(), "flags_out": flags_out.cpu().numpy(), "status": status.cpu().numpy(),
             "outgoing": slot_download(outgoing, s16), "plan": plan}
+
+
+def run_ag_gemm_k(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None, epoch=1, deliver="pre",
+                  order=None, timeout_us=0, withhold=None, act="none"):
+    """One pk_ag_gemm_k call.  chunks: list of P numpy bit arrays (M x K/P), chunk q = columns K_q of A.
+
+    deliver = "pre": every chunk is in A_gathered with its flag set before the call.
+    deliver = "dma": only the own chunk is in place, the others are poisoned; pk_emu_deliver_kchunks_dma copies them in on
+                     a second stream in `order` (strided copies + stream flag writes).
+    withhold: a chunk index whose flag is never set ("pre" only).
+    """
+    npdt = np.uint16 if dtype == "bf16" else np.uint8
+    elem = 2 if dtype == "bf16" else 1
+    poison = 0x7FC1 if dtype == "bf16" else 0x7F
+    kp = K // P
+    B = elem_view(B_bits, dtype)
+    sa, sb = scale_t(scale_a), scale_t(scale_b)
+    C = torch.full((M, N // P), -1, dtype=torch.int16, device="cuda")
+    flags = torch.zeros(P, dtype=torch.int32, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    peers = [q for q in range(P) if q != rank]
+    if order is None:
+        order = [(rank + d) % P for d in range(1, P)]
+    full = np.concatenate([np.asarray(c, dtype=npdt) for c in chunks], axis=1)
+    main = torch.cuda.current_stream()
+    if deliver == "pre":
+        A = elem_view(full, dtype)
+        for q in peers:
+            flags[q] = epoch
+        if withhold is not None:
+            flags[withhold] = epoch - 1
+        torch.cuda.synchronize()
+    else:
+        staging = elem_view(full, dtype)
+        start = np.full_like(full, poison)
+        start[:, rank * kp:(rank + 1) * kp] = full[:, rank * kp:(rank + 1) * kp]
+        A = elem_view(start, dtype)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        pk.pk_emu_deliver_kchunks_dma(P, M, K, elem, staging, A, flags, epoch, list(order), stream=side)
+    pk.pk_ag_gemm_k(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status, timeout_us,
+                    stream=main, act=act)
+    torch.cuda.synchronize()
+    return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy(), "flags": flags.cpu().numpy()}

@@ -194,3 +194,27 @@ def test_gemm_rs_cols_plan_and_argument_errors_launch_nothing():
     assert rs(phases=0) == pk.ERR_ARG
     assert rs(pdt=7) == pk.ERR_DTYPE
     assert rs(out=0x7001) == pk.ERR_ALIGN
+
+
+def test_ag_gemm_k_plan_and_argument_errors_launch_nothing():
+    p = pk.pk_ag_gemm_k_plan(8, 8192, 28672, 8192, "bf16")
+    assert (p.tile_m, p.tile_n, p.tiles_m, p.tiles_n) == (256, 256, 32, 14)
+    assert (p.local_m, p.local_n, p.local_k) == (8192, 3584, 8192)
+    p = pk.pk_ag_gemm_k_plan(4, 200, 4 * 264, 4 * 128, "bf16")              # M need not divide by P
+    assert (p.tile_m, p.tiles_m, p.tiles_n) == (128, 2, 3)
+    L = pk.lib()
+    plan = pk.Plan()
+    assert L.pk_ag_gemm_k_plan(4, 200, 1056, 4 * 96, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE          # (K/P) % 64
+    assert L.pk_ag_gemm_k_plan(4, 200, 1056, 510, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE             # K % P
+    assert L.pk_ag_gemm_k_plan(4, 200, 1058, 512, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE             # N % P
+
+    def ag(rank=0, A=0x1000, flags=0x3000, act=0):
+        return L.pk_ag_gemm_k(4, rank, 200, 1056, 512, pk.BF16, A, 0x2000, None, None, flags, 1, 0x4000, 0, act, 0x5000, 0, None)
+    assert ag(rank=4) == pk.ERR_RANK
+    assert ag(A=None) == pk.ERR_NULL
+    assert ag(flags=None) == pk.ERR_NULL
+    assert ag(act=9) == pk.ERR_ARG
+    order = (ctypes.c_int * 3)(1, 2, 3)
+    assert L.pk_emu_deliver_kchunks_dma(4, 200, 510, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, None) == pk.ERR_SHAPE
+    assert L.pk_emu_deliver_kchunks_dma(4, 200, 512, 2, None, 0x2000, 0x3000, 1, order, 3, None) == pk.ERR_NULL
+    assert L.pk_emu_deliver_kchunks_dma(4, 200, 512, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, None) == pk.OK

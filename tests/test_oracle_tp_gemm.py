@@ -244,6 +244,27 @@ def test_gemm_rs_cols_integer_brute_force_all_ranks(P, M, N, K):
                              np.zeros((P, M, np_ + 1), np.float32))
 
 
+def test_gather_along_the_last_dimension():
+    """Column chunk q holds columns K_q; the product with the column-gathered A equals the sum over chunks of
+    chunk_q . B[K_q, :] (integers: exactly), whatever the order the chunks are combined in."""
+    P, M, N, K = 3, 4, 5, 9
+    A = wl.small_int_matrix((M, K), 71, 1)
+    B = wl.small_int_matrix((K, N), 71, 2)
+    kp = K // P
+    chunks = [_int_bits(A[:, q * kp:(q + 1) * kp], "bf16") for q in range(P)]
+    G = tp_gemm.gather_kchunks(chunks)
+    assert G.shape == (M, K)
+    for q in range(P):
+        assert np.array_equal(G[:, q * kp:(q + 1) * kp], chunks[q])
+    full = np.array(_brute_int(A, B), dtype=np.float64)
+    got = tp_gemm.ag_gemm(P, 1, G, _int_bits(B, "bf16"), "bf16")["C"] if M % P == 0 else \
+        tp_gemm.local_product(G, _int_bits(B, "bf16"), "bf16")
+    assert np.array_equal(got, full)
+    by_chunk = sum(np.array(_brute_int(A[:, q * kp:(q + 1) * kp], B[q * kp:(q + 1) * kp, :]), dtype=np.float64)
+                   for q in (2, 0, 1))
+    assert np.array_equal(by_chunk, full)
+
+
 def test_activation_closed_forms_and_identities():
     x = np.linspace(-6, 6, 97)
     for kind in ("silu", "gelu_tanh"):
