@@ -223,7 +223,9 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         }
     };
 
-    uint64_t seen_chunks = 0;   // EPI_AGK: column chunks of A this workgroup has already waited for
+    // EPI_AGK: column chunks of A known to have landed (the own one, and those this workgroup has waited for)
+    uint64_t seen_chunks = 1ull << (g.rank & 63);
+    const uint64_t all_chunks = g.k_chunks >= 64 ? ~0ull : (1ull << g.k_chunks) - 1;
     int v = blockIdx.x;
     for (;;) {
         // ---- which tile (paper listing: interpret_task) ----
@@ -245,9 +247,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         const char* b_base = g.B;
         const int64_t b_step = (int64_t)B_ROWS * g.ldb;
         // k-tiles handled between two pipeline fills: all of them, or one column chunk of A at a time (EPI_AGK, own
-        // chunk first)
-        const int seg_ktiles = (EPI == EPI_AGK) ? g.ktiles / g.k_chunks : g.ktiles;
-        if constexpr (EPI == EPI_AGK) {
+        // chunk); once this workgroup has seen every chunk, its later tiles run the whole k range in one go
+        const bool by_chunk = (EPI == EPI_AGK) && seen_chunks != all_chunks;
+        const int seg_ktiles = by_chunk ? g.ktiles / g.k_chunks : g.ktiles;
+        if (by_chunk) {
             a_base += (int64_t)g.rank * seg_ktiles * KB;
             b_base += (int64_t)g.rank * seg_ktiles * b_step;
         }
@@ -514,7 +517,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             ktile(kt, std::false_type{}, std::false_type{});
         };
         run_ktiles(seg_ktiles);
-        if constexpr (EPI == EPI_AGK) {
+        if (by_chunk) {
             // the other column chunks of A, in ring order from the own one; the first tile that touches a chunk waits for
             // its flag (paper appendix C `wait`), later tiles of this workgroup know it has landed
             for (int sgm = 1; sgm < g.k_chunks; ++sgm) {
