@@ -103,7 +103,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     constexpr int KS = FP8 ? KB / 64 : KB / 32;          // MFMA k-steps per k-tile
     constexpr int EPI_OFF = NS * STAGE;                  // LDS offset of the epilogue staging area
     static_assert(KB == 64 || KB == 128, "k-tile is 64 or 128 bytes of A row");
-    static_assert(KS >= 2 && KS % 2 == 0, "the fragment double buffer needs an even number of k-steps");
+    static_assert(KS >= 1, "a k-tile holds at least one MFMA k-step");
     static_assert(CPR >= 8 && RPI >= 1, "tile too narrow");
     static_assert(NW % 2 == 0 && NA >= 1 && NB >= 1, "wave grid does not fit the tile");
     static_assert((NS - 2) * NL <= 63, "too many loads in flight for the counter");
@@ -493,28 +493,53 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        auto ktile = [&](int kt, auto loads_c, auto next_c) {
+        auto ktile = [&](int kt, auto loads_c, auto next_c, auto par_c) {
             constexpr bool LOADS = decltype(loads_c)::value;
+            constexpr int P0 = decltype(par_c)::value;   // fragment set that holds this k-tile's first fragments
             const int sidx = kt % NS;
             PK_LDS char* st = lds + sidx * STAGE;
             PK_LDS char* nx = lds + (sidx + 1 == NS ? 0 : sidx + 1) * STAGE;
-#pragma unroll
-            for (int kk = 0; kk < KS - 1; ++kk) {
-                if (kk & 1) kstep(af1, bf1, af0, bf0, st, kk + 1, std::true_type{}, 0, std::false_type{});
-                else kstep(af0, bf0, af1, bf1, st, kk + 1, std::true_type{}, 0, std::false_type{});
-            }
+            // fragment set `par` is consumed, the other one refilled
+            auto step = [&](auto par, PK_LDS char* rd_stage, int rd_kk, auto reads_c, int ld_stage, auto lds_c) {
+                if constexpr (decltype(par)::value) kstep(af1, bf1, af0, bf0, rd_stage, rd_kk, reads_c, ld_stage, lds_c);
+                else kstep(af0, bf0, af1, bf1, rd_stage, rd_kk, reads_c, ld_stage, lds_c);
+            };
+            if constexpr (KS >= 2) step(std::integral_constant<int, P0>{}, st, 1, std::true_type{}, 0, std::false_type{});
+            if constexpr (KS >= 3) step(std::integral_constant<int, P0 ^ 1>{}, st, 2, std::true_type{}, 0, std::false_type{});
+            if constexpr (KS >= 4) step(std::integral_constant<int, P0>{}, st, 3, std::true_type{}, 0, std::false_type{});
+            static_assert(KS <= 4, "at most four k-steps per k-tile");
             if constexpr (LOADS) __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0((NS - 2) * NL));
             else __builtin_amdgcn_s_waitcnt(waitcnt_vm_lgkm0(0));
             __syncthreads();
-            kstep(af1, bf1, af0, bf0, nx, 0, next_c, sidx, loads_c);
+            step(std::integral_constant<int, (P0 + KS - 1) & 1>{}, nx, 0, next_c, sidx, loads_c);
         };
         // the k-tiles of one pipeline fill: the first NS are in flight or landed, stage 0 holds the first
         auto run_ktiles = [&](int nkt) {
+            using T = std::true_type;
+            using F = std::false_type;
+            using E = std::integral_constant<int, 0>;    // k-tile starts on fragment set 0
+            using O = std::integral_constant<int, 1>;    // ... on set 1
             load_frags(lds, 0, af0, bf0);
             int kt = 0;
-            for (; kt + NS < nkt; ++kt) ktile(kt, std::true_type{}, std::true_type{});
-            for (; kt + 1 < nkt; ++kt) ktile(kt, std::false_type{}, std::true_type{});
-            ktile(kt, std::false_type{}, std::false_type{});
+            if constexpr (KS % 2 == 0) {
+                for (; kt + NS < nkt; ++kt) ktile(kt, T{}, T{}, E{});
+                for (; kt + 1 < nkt; ++kt) ktile(kt, F{}, T{}, E{});
+                ktile(kt, F{}, F{}, E{});
+            } else {
+                // odd k-steps per k-tile: the starting set alternates, so k-tiles go in pairs (nkt and NS are even: the
+                // host admits only k ranges of whole 128-byte units)
+                static_assert(KS % 2 == 0 || NS % 2 == 0, "pairs of k-tiles need an even ring");
+                for (; kt + NS < nkt; kt += 2) {
+                    ktile(kt, T{}, T{}, E{});
+                    ktile(kt + 1, T{}, T{}, O{});
+                }
+                for (; kt + 2 < nkt; kt += 2) {
+                    ktile(kt, F{}, T{}, E{});
+                    ktile(kt + 1, F{}, T{}, O{});
+                }
+                ktile(kt, F{}, T{}, E{});
+                ktile(kt + 1, F{}, F{}, O{});
+            }
         };
         run_ktiles(seg_ktiles);
         if (by_chunk) {

@@ -352,8 +352,8 @@ template <int EPI>
 static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const TileCfg& tc, bool fp8,
                                hipStream_t stream) {
     if (tc.bm == 256) {
-        // bf16: 8 waves, 64-byte k-tiles in a ring of 4 LDS stages; fp8: 128-byte k-tiles, 2 stages
-        return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI>(a, slots, comm_cus, stream)
+        // 8 waves, 64-byte k-tiles (32 bf16 or 64 fp8 of k) in a ring of 4 LDS stages
+        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, stream)
                    : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, stream);
     }
     return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, stream)
