@@ -418,7 +418,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                                     const int ch = colw >> 3;                  // 16-byte chunk (8 bf16)
                                     float x0 = acc[ti][tj][4 * b] * scale, x1 = acc[ti][tj][4 * b + 1] * scale,
                                           x2 = acc[ti][tj][4 * b + 2] * scale, x3 = acc[ti][tj][4 * b + 3] * scale;
-                                    if constexpr (!IS_RS) {
+                                    if constexpr (!IS_RS) if (g.act != PK_ACT_NONE) {
                                         x0 = activate(x0);
                                         x1 = activate(x1);
                                         x2 = activate(x2);

@@ -1,6 +1,8 @@
 // libpk: kernels other than the GEMM, and the C-ABI entry points (see include/pk.h).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "pk_device.h"
 #include "pk_gemm.h"
 
@@ -312,15 +314,16 @@ static pk_status make_plan_cols(int P, int64_t M, int64_t N, int64_t K, pk_dtype
     return PK_OK;
 }
 
+// compute units of the current device (cached per device ordinal)
 static int num_cus() {
-    static int n = 0;
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = cache[dev].load(std::memory_order_relaxed);
     if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            n = v;
-        else
-            n = 256;
+        int v = 0;
+        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+        cache[dev].store(n, std::memory_order_relaxed);
     }
     return n;
 }
@@ -329,14 +332,18 @@ static int num_cus() {
 // when there are fewer tile slots.
 template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
 static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, hipStream_t stream) {
-    static bool configured = false;
+    // the dynamic LDS size of this instantiation is raised once per device (bit d of `configured` = done on device d)
+    static std::atomic<uint64_t> configured{0};
     auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI>;
     constexpr int lds = gemm_lds_bytes<BM, BN, KB, NS>();
     a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
-    if (!configured) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PK_ERR_HIP;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(configured.load(std::memory_order_acquire) & bit)) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return PK_ERR_HIP;
-        configured = true;
+        configured.fetch_or(bit, std::memory_order_release);
     }
     int grid = (num_cus() - comm_cus) / 8 * 8;
     if (grid < 8) grid = 8;
