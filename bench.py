@@ -378,9 +378,14 @@ def extras(pk, wl, torch, np, L):
                       L["status"])
         stream.wait_stream(side2)
     t_dma = timeit(ag_live_dma)
+    ring = list(order)
+    order = ring[::-1]                      # adversarial: the chunk the schedule wants first arrives last
+    t_dma_rev = timeit(ag_live_dma)
+    order = ring
     t_dma_alone = timeit(lambda: pk.pk_emu_deliver_chunks_dma(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_dma, 1, order,
                                                                stream=stream))
-    out["ag_gemm_live_copy_engine"] = {"ms_live_ring_arrival": round(t_dma, 4), "ms_copies_alone": round(t_dma_alone, 4),
+    out["ag_gemm_live_copy_engine"] = {"ms_live_ring_arrival": round(t_dma, 4), "ms_live_reverse_arrival": round(t_dma_rev, 4),
+                                       "ms_copies_alone": round(t_dma_alone, 4),
                                        "TFLOP/s_live": round(c4.flops / (t_dma * 1e-3) / 1e12, 1)}
 
     # all-gather along the last dimension of A (column chunks, strided copies) at the cfg4 shape

@@ -223,38 +223,39 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         }
     };
 
-    // EPI_AGK: column chunks of A known to have landed (the own one, and those this workgroup has waited for)
+    // chunks of A known to have landed (the own one, and those this workgroup has waited for): EPI_AG, EPI_AGK
     uint64_t seen_chunks = 1ull << (g.rank & 63);
     const uint64_t all_chunks = g.k_chunks >= 64 ? ~0ull : (1ull << g.k_chunks) - 1;
     int v = blockIdx.x;
+    // EPI_AG: a slot whose chunk has not landed when it is first visited is put aside (bit i = this workgroup's i-th slot)
+    // and taken up again, now waiting, once the workgroup has gone through its other slots: tiles of chunks that are
+    // already there never queue behind a late one.  Slots beyond the 64th wait on the spot.
+    uint64_t deferred = 0;
+    int visit = 0;
     for (;;) {
         // ---- which tile (paper listing: interpret_task) ----
-        int t = 0, gi = 0;
+        int q = 0, tmi = 0, tc = 0, row0 = 0, row_end = 0, col0 = 0, col_end = 0, flag = 0;
         bool have = false;
-        while (v < slots_total) {
-            gi = v / g.wg_per_group;
-            const int u = v - gi * g.wg_per_group;
-            t = (u & 7) * (g.wg_per_group >> 3) + (u >> 3);
-            v += gridDim.x;
-            if (t < G) {
-                have = true;
+        for (;;) {
+            int slot, slot_index;
+            bool may_defer = false;
+            if (v < slots_total) {
+                slot = v;
+                slot_index = visit;
+                v += gridDim.x;
+                ++visit;
+                may_defer = (EPI == EPI_AG) && slot_index < 64;
+            } else if ((EPI == EPI_AG) && deferred != 0) {
+                slot_index = __builtin_ctzll(deferred);
+                deferred &= deferred - 1;
+                slot = (int)blockIdx.x + slot_index * (int)gridDim.x;
+            } else {
                 break;
             }
-        }
-        int q = 0, tmi = 0, tc = 0, row0 = 0, row_end = 0, col0 = 0, col_end = 0, flag = 0;
-        uint32_t a_voff[NA], b_voff[NB];           // per-lane byte offsets from the k-tile base pointers
-        const char* a_base = g.A;                    // wave-uniform, advanced by one k-tile per issue
-        const char* b_base = g.B;
-        const int64_t b_step = (int64_t)B_ROWS * g.ldb;
-        // k-tiles handled between two pipeline fills: all of them, or one column chunk of A at a time (EPI_AGK, own
-        // chunk); once this workgroup has seen every chunk, its later tiles run the whole k range in one go
-        const bool by_chunk = (EPI == EPI_AGK) && seen_chunks != all_chunks;
-        const int seg_ktiles = by_chunk ? g.ktiles / g.k_chunks : g.ktiles;
-        if (by_chunk) {
-            a_base += (int64_t)g.rank * seg_ktiles * KB;
-            b_base += (int64_t)g.rank * seg_ktiles * b_step;
-        }
-        if (have) {
+            const int gi = slot / g.wg_per_group;
+            const int u = slot - gi * g.wg_per_group;
+            const int t = (u & 7) * (g.wg_per_group >> 3) + (u >> 3);
+            if (t >= G) continue;
             const int BAND = g.band > 0 ? g.band : 1;
             const int band = t / (BAND * g.tiles_n);
             const int rem = t - band * BAND * g.tiles_n;
@@ -280,25 +281,57 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                     flag = tmi * g.tiles_n_shard + tci;
                 }
             }
+            have = true;
 
-            // all-gather: wait until the chunk this tile reads has landed
+            // all-gather: the chunk this tile reads must have landed (paper appendix C `wait`)
             if constexpr (EPI == EPI_AG) {
-                if (q != g.rank) {
-                    // lane 0 polls; the verdict goes through a word of the (idle) epilogue staging area,
-                    // since the kernel leaves no LDS for a static variable
+                if (!((seen_chunks >> (q & 63)) & 1)) {
+                    // lane 0 polls; the verdict (0 landed, 1 timed out, 2 not yet: put the slot aside) goes through a
+                    // word of the (idle) epilogue staging area, since the kernel leaves no LDS for a static variable
                     PK_LDS int* verdict = (PK_LDS int*)(lds + EPI_OFF);
                     if (tid == 0) {
-                        const int late = flag_wait(g.chunk_flags + q, g.epoch, g.timeout_ticks) ? 0 : 1;
-                        if (late) report_timeout(g.status, (uint32_t)q, 1u);
-                        *verdict = late;
+                        int vd = 0;
+                        if (!flag_ready(g.chunk_flags + q, g.epoch)) {
+                            if (may_defer) {
+                                vd = 2;
+                            } else if (!flag_wait(g.chunk_flags + q, g.epoch, g.timeout_ticks)) {
+                                report_timeout(g.status, (uint32_t)q, 1u);
+                                vd = 1;
+                            }
+                        }
+                        *verdict = vd;
                     }
                     __syncthreads();
-                    const int late_all = *verdict;
+                    const int vd_all = *verdict;
                     __syncthreads();
-                    if (late_all) have = false;                 // drain: this tile's rows stay untouched
-                    else acquire_agent();
+                    if (vd_all == 2) {
+                        deferred |= 1ull << slot_index;
+                        have = false;
+                        continue;
+                    }
+                    if (vd_all == 1) {
+                        have = false;                       // drain: this tile's and the later tiles' rows stay untouched
+                        v = slots_total;
+                        deferred = 0;
+                        break;
+                    }
+                    acquire_agent();
+                    if (q < 64) seen_chunks |= 1ull << q;
                 }
             }
+            break;
+        }
+        uint32_t a_voff[NA], b_voff[NB];           // per-lane byte offsets from the k-tile base pointers
+        const char* a_base = g.A;                    // wave-uniform, advanced by one k-tile per issue
+        const char* b_base = g.B;
+        const int64_t b_step = (int64_t)B_ROWS * g.ldb;
+        // k-tiles handled between two pipeline fills: all of them, or one column chunk of A at a time (EPI_AGK, own
+        // chunk); once this workgroup has seen every chunk, its later tiles run the whole k range in one go
+        const bool by_chunk = (EPI == EPI_AGK) && seen_chunks != all_chunks;
+        const int seg_ktiles = by_chunk ? g.ktiles / g.k_chunks : g.ktiles;
+        if (by_chunk) {
+            a_base += (int64_t)g.rank * seg_ktiles * KB;
+            b_base += (int64_t)g.rank * seg_ktiles * b_step;
         }
         if (have) {
             // per-lane global source addresses of the direct-to-LDS loads.  Wave-wide load j of wave w fills
