@@ -503,6 +503,41 @@ def extras(pk, wl, torch, np, L):
     t_cols = timeit(rs_cols)
     out["gemm_rs_last_dim_cfg3_shape"] = {"ms": round(t_cols, 4), "TFLOP/s": round(c3.flops / (t_cols * 1e-3) / 1e12, 1)}
 
+    # the two small configurations are launch-latency bound: per-call time eager and as a HIP graph replay
+    c1, c2 = wl.CONFIGS["cfg1"], wl.CONFIGS["cfg2"]
+    i1 = wl.gemm_rs_inputs(c1.P, c1.M, c1.N, c1.K, c1.dtype, 0, seed=0)
+    i2 = wl.ag_gemm_inputs(c2.P, c2.M, c2.N, c2.K, c2.dtype, 0, seed=0, order=c2.order)
+    p1 = pk.pk_gemm_rs_plan(c1.P, c1.M, c1.N, c1.K, c1.dtype)
+    A1, B1 = torch.from_numpy(i1["A_local"].view(np.int16)).cuda(), torch.from_numpy(i1["B_local"].view(np.int16)).cuda()
+    part1 = torch.from_numpy(i1["partials"]).cuda()
+    outg1 = torch.zeros_like(part1)
+    fin1 = torch.full((c1.P, p1.flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    fin1[0].zero_()
+    fout1 = torch.zeros_like(fin1)
+    out1 = torch.zeros((c1.M // c1.P, c1.N), dtype=torch.int16, device="cuda")
+    A2 = torch.from_numpy(np.concatenate(i2["chunks"], axis=0).view(np.int16)).cuda()
+    B2 = torch.from_numpy(i2["B_local"].view(np.int16)).cuda()
+    C2 = torch.zeros((c2.M, c2.N // c2.P), dtype=torch.int16, device="cuda")
+    cf2 = torch.full((c2.P,), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+
+    def small(st=None):
+        pk.pk_gemm_rs(c1.P, 0, c1.M, c1.N, c1.K, c1.dtype, A1, B1, None, None, part1, outg1, fin1, fout1, 1, out1,
+                      pk.PHASE_ALL, L["status"], stream=st)
+        pk.pk_ag_gemm(c2.P, 0, c2.M, c2.N, c2.K, c2.dtype, A2, B2, None, None, cf2, 1, C2, L["status"], stream=st)
+    t_small = timeit(small, n=50, w=5)
+    gs = torch.cuda.Stream()
+    gs.wait_stream(stream)
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(gs):
+        small(gs)
+        gs.synchronize()
+        with torch.cuda.graph(gr, stream=gs):
+            small(gs)
+    torch.cuda.synchronize()
+    t_graph = timeit(gr.replay, n=50, w=5)
+    out["small_configs_cfg1_plus_cfg2"] = {"us_eager": round(t_small * 1e3, 1), "us_hip_graph_replay": round(t_graph * 1e3, 1),
+                                           "kernels_per_call": 3}
+
     # the paper's own element size for communicated tiles (s = 2): bf16 partial slots halve scatter and reduce traffic
     out["bf16_partial_slots"] = {}
     for name, c, A, B, sa, sb, part32, fin, fout, o in (("cfg3", c3, L["A3"], L["B3"], None, None, L["part"], L["flags_in"],
