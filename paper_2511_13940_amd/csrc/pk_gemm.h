@@ -412,20 +412,6 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             char* dst_base;
             int64_t dst_pitch;
             int dst_row0;                                    // global row -> row inside the destination
-            // the activation is applied to the accumulators in one block of its own, skipped by a single branch when none
-            // is asked for: its transcendental code stays out of the instruction stream of the stores below
-            float out_scale = scale;
-            if constexpr (!IS_RS) {
-                if (g.act != PK_ACT_NONE) {
-#pragma unroll
-                    for (int ti = 0; ti < TM; ++ti)
-#pragma unroll
-                        for (int tj = 0; tj < TN; ++tj)
-#pragma unroll
-                            for (int e = 0; e < 16; ++e) acc[ti][tj][e] = activate(acc[ti][tj][e] * scale);
-                    out_scale = 1.f;
-                }
-            }
             int dst_col0 = 0;                                // global column -> column inside the destination
             if constexpr (IS_RS) {
                 dst_base = (p_q == g.rank) ? (char*)g.partials + (int64_t)g.rank * g.slot_elems * OUT_ELEM
@@ -458,13 +444,20 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                                 const int colw = tj * 32 + 8 * b + 4 * h;     // column inside the wave sub-tile
                                 if constexpr (EPI == EPI_RS) {
                                     const int ch = colw >> 2;                  // 16-byte chunk (4 floats)
-                                    f32x4 val = {acc[ti][tj][4 * b] * out_scale, acc[ti][tj][4 * b + 1] * out_scale,
-                                                 acc[ti][tj][4 * b + 2] * out_scale, acc[ti][tj][4 * b + 3] * out_scale};
+                                    f32x4 val = {acc[ti][tj][4 * b] * scale, acc[ti][tj][4 * b + 1] * scale,
+                                                 acc[ti][tj][4 * b + 2] * scale, acc[ti][tj][4 * b + 3] * scale};
                                     *(PK_LDS f32x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16)) = val;
                                 } else {
                                     const int ch = colw >> 3;                  // 16-byte chunk (8 bf16)
-                                    bf16x4 val = {(__bf16)(acc[ti][tj][4 * b] * out_scale), (__bf16)(acc[ti][tj][4 * b + 1] * out_scale),
-                                                  (__bf16)(acc[ti][tj][4 * b + 2] * out_scale), (__bf16)(acc[ti][tj][4 * b + 3] * out_scale)};
+                                    float x0 = acc[ti][tj][4 * b] * scale, x1 = acc[ti][tj][4 * b + 1] * scale,
+                                          x2 = acc[ti][tj][4 * b + 2] * scale, x3 = acc[ti][tj][4 * b + 3] * scale;
+                                    if constexpr (!IS_RS) if (g.act != PK_ACT_NONE) {
+                                        x0 = activate(x0);
+                                        x1 = activate(x1);
+                                        x2 = activate(x2);
+                                        x3 = activate(x3);
+                                    }
+                                    bf16x4 val = {(__bf16)x0, (__bf16)x1, (__bf16)x2, (__bf16)x3};
                                     *(PK_LDS bf16x4*)(stg + rs * ROW_BYTES + ((ch ^ (rs & (CH - 1))) * 16) + (h * 8)) = val;
                                 }
                             }
