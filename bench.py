@@ -568,6 +568,38 @@ def extras(pk, wl, torch, np, L):
             "ms": round(t_all, 4), "gemm_phase_ms": round(t_g, 4), "reduce_phase_ms": round(t_r, 4),
             "TFLOP/s": round(c.flops / (t_all * 1e-3) / 1e12, 1),
             "max_abs_diff_vs_fp32_slots_over_rms": round(((got - ref).abs().max() / ref.pow(2).mean().sqrt()).item(), 5)}
+    # the paper's Table 3 (section 3.1.3) at its own sizes: M = N = 32768 per rank, local K from 512 to 8192, P = 8; bare
+    # GEMM (bf16 output) against GEMM + reduce-scatter (fp32 slots, peers pre-landed); operands drawn on the device
+    P8, MN = 8, 32768
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(251113940)
+    mp8 = MN // P8
+    part_t = torch.randn((P8, mp8, MN), generator=gen, device="cuda", dtype=torch.float32) * 0.01
+    outg_t = torch.empty_like(part_t)
+    out_t = torch.zeros((mp8, MN), dtype=torch.int16, device="cuda")
+    C_t = torch.zeros((MN, MN), dtype=torch.int16, device="cuda")
+    out["table3_paper_sizes"] = {}
+    ept = [10 * 10 ** 6]
+    for kl in (512, 1024, 2048, 4096, 8192):
+        At = (torch.randn((MN, kl), generator=gen, device="cuda") / (P8 * kl) ** 0.5).to(torch.bfloat16).view(torch.int16)
+        Bt = (torch.randn((kl, MN), generator=gen, device="cuda") / (P8 * kl) ** 0.5).to(torch.bfloat16).view(torch.int16)
+        pt = pk.pk_gemm_rs_plan(P8, MN, MN, P8 * kl, "bf16")
+        fin_t = torch.full((P8, pt.flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+        fin_t[rank].zero_()
+        fout_t = torch.zeros_like(fin_t)
+
+        def rs_t():
+            ept[0] += 1
+            pk.pk_gemm_rs(P8, rank, MN, MN, P8 * kl, "bf16", At, Bt, None, None, part_t, outg_t, fin_t, fout_t, ept[0], out_t,
+                          pk.PHASE_ALL, L["status"])
+        t_g = timeit(lambda: pk.pk_ag_gemm(1, 0, MN, MN, kl, "bf16", At, Bt, None, None, None, 1, C_t, L["status"]), n=5, w=2)
+        t_f = timeit(rs_t, n=5, w=2)
+        fl = 2.0 * MN * MN * kl
+        out["table3_paper_sizes"][f"K={kl}"] = {"gemm_ms": round(t_g, 3), "gemm_rs_ms": round(t_f, 3),
+                                                "comm_ratio": round((t_f - t_g) / t_f, 3),
+                                                "gemm_TFLOP/s": round(fl / (t_g * 1e-3) / 1e12, 1),
+                                                "gemm_rs_TFLOP/s": round(fl / (t_f * 1e-3) / 1e12, 1)}
+        del At, Bt
     assert L["status"][0].item() == 0
     return out
 

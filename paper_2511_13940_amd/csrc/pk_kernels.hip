@@ -58,9 +58,12 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     if (__syncthreads_or(late)) return;
 
     constexpr int SLOT_ELEM = S16 ? 2 : 4;
+    // one buffer descriptor per slot (a slot stays below 4 GiB, all P together need not)
     const uint32_t slot_bytes = (uint32_t)(r.slot_elems * SLOT_ELEM);
-    __amdgpu_buffer_rsrc_t src = __builtin_amdgcn_make_buffer_rsrc((void*)r.partials, 0, (int)(slot_bytes * (uint32_t)P),
-                                                                   0x00020000);
+    auto slot = [&](int p) {
+        return __builtin_amdgcn_make_buffer_rsrc((char*)r.partials + (int64_t)p * r.slot_elems * SLOT_ELEM, 0, (int)slot_bytes,
+                                                 0x00020000);
+    };
     const int row_start = tmi * r.tile_m + sb * r.rows_sub;
     const int row_stop = min(min(row_start + r.rows_sub, (tmi + 1) * r.tile_m), r.rows);
     const int col0 = tc * r.tile_n;
@@ -92,18 +95,18 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
             if constexpr (PT > 0) {
                 i32x4 v[PT];
 #pragma unroll
-                for (int p = 0; p < PT; ++p) v[p] = __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream);
+                for (int p = 0; p < PT; ++p) v[p] = __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff, 0, kCoherentStream);
 #pragma unroll
                 for (int p = 0; p < PT; ++p) add16(s0, s1, v[p]);
             } else {
-                for (int p = 0; p < P; ++p) add16(s0, s1, __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream));
+                for (int p = 0; p < P; ++p) add16(s0, s1, __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff, 0, kCoherentStream));
             }
         } else if constexpr (PT > 0) {
             f32x4 v0[PT], v1[PT];
 #pragma unroll
             for (int p = 0; p < PT; ++p) {
-                v0[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream));
-                v1[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff + 16, p * slot_bytes, kCoherentStream));
+                v0[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff, 0, kCoherentStream));
+                v1[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff + 16, 0, kCoherentStream));
             }
             s0 = v0[0];
             s1 = v1[0];
@@ -113,11 +116,11 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
                 s1 += v1[p];
             }
         } else {
-            s0 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff, 0, kCoherentStream));
-            s1 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff + 16, 0, kCoherentStream));
+            s0 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(0), boff, 0, kCoherentStream));
+            s1 = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(0), boff + 16, 0, kCoherentStream));
             for (int p = 1; p < P; ++p) {
-                s0 += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff, p * slot_bytes, kCoherentStream));
-                s1 += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(src, boff + 16, p * slot_bytes, kCoherentStream));
+                s0 += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff, 0, kCoherentStream));
+                s1 += __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff + 16, 0, kCoherentStream));
             }
         }
         bf16x8 o = {(__bf16)s0[0], (__bf16)s0[1], (__bf16)s0[2], (__bf16)s0[3],
@@ -266,9 +269,10 @@ static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt,
     if (k % kt || n % nv) return PK_ERR_SHAPE;
     if (ag_k && (K % P || (K / P) % kt)) return PK_ERR_SHAPE;   // A arrives in column chunks of whole k-tiles
     if (m > (1 << 30) || n > (1 << 30) || k > (1 << 30)) return PK_ERR_SHAPE;
-    // the kernels address each operand, and the fp32 partial slots, with 32-bit byte offsets from their base
+    // the kernels address each operand, and each partial slot (M*N/P elements, at most 4 bytes each), with 32-bit byte
+    // offsets from its base
     if (m * k * 2 >= ((int64_t)1 << 32) || k * n * 2 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
-    if (rs && m * n * 4 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
+    if (rs && m * n / P * 4 >= ((int64_t)1 << 32)) return PK_ERR_SHAPE;
     *lm = m;
     *ln = n;
     *lk = k;

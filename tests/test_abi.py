@@ -167,6 +167,17 @@ def test_partition_and_probe_argument_errors_launch_nothing():
     assert L.pk_probe_mfma(0, 1, 0x1000, None, None) == pk.ERR_ARG
 
 
+def test_size_limits():
+    """32-bit byte offsets inside one operand and inside one partial slot; the slots together may exceed 4 GiB."""
+    p = pk.pk_gemm_rs_plan(8, 32768, 32768, 8 * 8192, "bf16")                  # the paper's Table 3 size: 8 slots of 512 MiB
+    assert (p.tiles_m, p.tiles_n, p.local_k) == (16, 128, 8192)
+    plan = pk.Plan()
+    L = pk.lib()
+    assert L.pk_gemm_rs_plan(2, 65536, 32768, 2 * 64, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE     # one slot = 4 GiB
+    assert L.pk_gemm_rs_plan(8, 32768, 32768, 8 * 65536, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE  # A_local = 4 GiB
+    assert L.pk_ag_gemm_plan(8, 32768, 8 * 8192, 65536, pk.BF16, ctypes.byref(plan)) == pk.ERR_SHAPE   # A_gathered = 4 GiB
+
+
 def test_binding_raises_pk_error():
     with pytest.raises(pk.PkError) as e:
         pk.pk_gemm_rs_plan(3, 256, 256, 512, "bf16")

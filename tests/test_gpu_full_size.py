@@ -94,3 +94,49 @@ def test_ag_gemm_full_size_sampled_rows(name, rank):
     assert not np.isnan(got).any()
     assert gate_err(got, ref) <= GATE[c.dtype]
     assert np.all(np.abs(got - ref) <= 2 * c.K * U32 * mag + 2.0 ** -8 * np.abs(ref) + 2.0 ** -133)
+
+
+def test_gemm_rs_at_the_papers_table3_size_sampled_rows():
+    """M = N = 32768, P = 8 (section 3.1.3, Table 3): the partial slots total 4 GiB, beyond 32-bit byte offsets.
+    The 7 peer slots are drawn on the device (seeded); the oracle gets the sampled rows of them."""
+    P, rank, MN, kl = 8, 5, 32768, 512
+    plan = pk.pk_gemm_rs_plan(P, MN, MN, P * kl, "bf16")
+    assert (plan.tile_m, plan.tiles_m, plan.tiles_n) == (256, 16, 128)
+    rng = np.random.default_rng([251113940, 33, 1])
+    A_bits = wl.to_bf16_bits((rng.standard_normal((MN, kl)) / np.sqrt(P * kl)).astype(np.float32))
+    B_bits = wl.to_bf16_bits((rng.standard_normal((kl, MN)) / np.sqrt(P * kl)).astype(np.float32))
+    A, B = hz.elem_view(A_bits, "bf16"), hz.elem_view(B_bits, "bf16")
+    mp = MN // P
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(33)
+    part = torch.randn((P, mp, MN), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+    part[rank].fill_(float("nan"))
+    outgoing = torch.full((P, mp, MN), float("nan"), dtype=torch.float32, device="cuda")
+    flags_in = torch.full((P, plan.flags_per_slot), 3, dtype=torch.int32, device="cuda")
+    flags_in[rank].zero_()
+    flags_out = torch.zeros_like(flags_in)
+    out = torch.full((mp, MN), -1, dtype=torch.int16, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    pk.pk_gemm_rs(P, rank, MN, MN, P * kl, "bf16", A, B, None, None, part, outgoing, flags_in, flags_out, 3, out,
+                  pk.PHASE_ALL, status)
+    torch.cuda.synchronize()
+    assert status[0].item() == 0
+    assert torch.all(flags_in[rank] == 3) and torch.all(flags_out[(rank + 1) % P] == 3)
+    rows = sample_rows(MN, P, 256, seed=3, extra=8)[::3]
+    own_rows = tp_gemm.local_product(A_bits, B_bits, "bf16", rows=rows)
+    mag = tp_gemm.abs_product(A_bits, B_bits, "bf16", rows=rows)
+    out_bits = hz.bits_of(out)
+    for t, i in enumerate(rows):
+        q, ii = int(i // mp), int(i % mp)
+        got32 = (part if q == rank else outgoing)[q, ii].cpu().numpy()
+        assert not np.isnan(got32).any()
+        assert np.all(np.abs(got32 - own_rows[t]) <= 2 * kl * U32 * mag[t] + 1e-30), i
+        if q == rank:
+            slots = [part[p, ii].cpu().numpy().astype(np.float64) for p in range(P) if p != rank]
+            want = own_rows[t] + sum(slots)
+            got = codec.bf16_decode(out_bits[ii])
+            assert gate_err(got, want) <= GATE["bf16"]
+            slot_mag = np.abs(own_rows[t]) + sum(np.abs(x) for x in slots)
+            assert np.all(np.abs(got - want) <= 2 * kl * U32 * mag[t] + P * U32 * slot_mag + 2.0 ** -8 * np.abs(want) + 2.0 ** -133)
+    # the last row of the last slot lies beyond the 4 GiB mark of both arrays
+    assert not torch.isnan(outgoing[P - 1 if rank != P - 1 else P - 2, mp - 1]).any()
