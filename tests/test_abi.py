@@ -229,3 +229,22 @@ def test_ag_gemm_k_plan_and_argument_errors_launch_nothing():
     assert L.pk_emu_deliver_kchunks_dma(4, 200, 510, 2, 0x1000, 0x2000, 0x3000, 1, order, 3, None) == pk.ERR_SHAPE
     assert L.pk_emu_deliver_kchunks_dma(4, 200, 512, 2, None, 0x2000, 0x3000, 1, order, 3, None) == pk.ERR_NULL
     assert L.pk_emu_deliver_kchunks_dma(4, 200, 512, 2, 0x1000, 0x2000, 0x3000, 1, order, 0, None) == pk.OK
+
+
+def test_header_and_library_work_from_plain_c(tmp_path):
+    """include/pk.h compiles as C99 and a C program linked against libpk.so gets the same answers."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    here = os.path.dirname(os.path.abspath(__file__))
+    root = os.path.dirname(here)
+    libdir = os.path.dirname(pk.LIB_PATH)
+    exe = str(tmp_path / "c_abi_check")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-I", os.path.join(root, "include"), os.path.join(here, "c_abi_check.c"),
+                    "-L", libdir, "-l:libpk.so", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib",
+                    "-Wl,--allow-shlib-undefined", "-o", exe], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, (out.returncode, out.stdout, out.stderr)
+    assert "c abi ok" in out.stdout
