@@ -3,6 +3,10 @@
  *
  *   pk_gemm_rs  GEMM + tile-granular reduce-scatter   (paper sections 3.1.3 and 4.1, figure "GEMM + RS")
  *   pk_ag_gemm  all-gather + GEMM                     (paper sections 3.1.3 and 4.1, figure "AG + GEMM")
+ * and, built on the same kernels,
+ *   pk_gemm_ar                       GEMM + all-reduce          (sections 3.1.3 and 4.1, figure "GEMM + AR")
+ *   pk_gemm_rs_cols, pk_ag_gemm_k    the scatter / gather along the last dimension (appendix on tensor-dimension collectives)
+ *   pk_partition_create              compute-unit partition for communicator workgroups (section 3.1.3, SM partitioning)
  *
  * Notation is the paper's (section 4, experimental setup): P ranks; the GLOBAL GEMM is M x N x K with a
  * first operand A of M x K and a second operand B of K x N; 16-bit (bf16) inputs, fp32 accumulation.  The
@@ -17,16 +21,20 @@
  *
  * Flags (the paper's barrier objects and signal/wait primitives, section 3.2.2 and appendix C): a flag is a
  * uint32 in device memory.  A datum is ready for a call with epoch e once (int32)(flag - e) >= 0.  Producers
- * write the data, release at device scope, then store e; consumers poll, acquire, then read the data.  Using a
- * monotone epoch instead of a counter that must be reset lets back-to-back calls reuse the flag arrays.
+ * make the data visible at device scope (write-through stores that have completed, or a release), then store e;
+ * consumers poll, acquire (or read past their L2), then read the data.  Using a monotone epoch instead of a
+ * counter that must be reset lets back-to-back calls reuse the flag arrays.
  *
  * Conventions for every entry point:
  *   - all pointers are DEVICE pointers unless marked "host";
- *   - the caller owns every buffer; the library allocates no device memory and keeps no state;
+ *   - the caller owns every buffer; the library allocates no device memory and keeps no state beyond per-device
+ *     launch attributes set on a kernel's first use;
  *   - calls are asynchronous on `stream` (a hipStream_t, passed as void*); nothing synchronises the device;
  *   - arguments are validated on the host first; on an error nothing is launched and nothing is written;
  *   - a wait that exceeds `timeout_us` microseconds makes the kernel write {PK_ERR_TIMEOUT, index, phase, 0}
  *     to status[0..3] (first error wins) and drain; the host reads it after synchronising the stream.
+ *     phase 1: a GEMM waiting for a chunk of A (index = chunk); phase 2: the reduce waiting for a tile's partials
+ *     (index = tile); phase 3: pk_gemm_ar's closing wait (index = flag).
  *     timeout_us = 0 selects the default (2 s).  The caller zeroes `status` (4 x uint32) before the call.
  */
 #ifndef PK_H
