@@ -195,3 +195,18 @@ def test_chunks_delivered_by_copies_and_stream_flag_writes():
         assert np.array_equal(res["C_bits"], base["C_bits"])
         assert np.array_equal(res["A_after"].view(np.uint16), full)
         assert np.all(res["flags"][order] == i + 1)
+
+
+def test_ten_seeded_arrival_orders_of_seven_chunks_bitwise_identical():
+    """P = 8: ten seeded permutations of the 7 peer chunks with different gaps, delivered into poisoned rows while the
+    GEMM runs (each workgroup meets several chunks): bit-identical to the pre-landed run, no NaN."""
+    P, rank, M, N, K = 8, 3, 8 * 256, 8 * 128, 256
+    inp = wl.ag_gemm_inputs(P, M, N, K, "bf16", rank, seed=61)
+    base = hz.run_ag_gemm(P, rank, M, N, K, "bf16", inp["chunks"], inp["B_local"])
+    check_ag(P, rank, "bf16", inp, base, K)
+    for s in range(10):
+        order = wl.arrival_order(P, rank, "random", seed=100 + s)
+        res = hz.run_ag_gemm(P, rank, M, N, K, "bf16", inp["chunks"], inp["B_local"], deliver="emu", order=order,
+                             gap_us=(0, 20, 120)[s % 3], epoch=s + 1, fetch_A=False)
+        assert res["status"][0] == 0
+        assert np.array_equal(res["C_bits"], base["C_bits"]), f"order {order}"

@@ -133,7 +133,7 @@ def test_arrival_order_independence_and_no_early_reads():
     inp = wl.gemm_rs_inputs(P, M, N, K, "bf16", rank, seed=13)
     base = hz.run_gemm_rs(P, rank, M, N, K, "bf16", inp["A_local"], inp["B_local"], inp["partials"])
     check_rs(P, rank, "bf16", inp, base, K // P)
-    for s in range(6):
+    for s in range(10):
         order = wl.arrival_order(P, rank, "random", seed=s)
         res = hz.run_gemm_rs(P, rank, M, N, K, "bf16", inp["A_local"], inp["B_local"], inp["partials"],
                              deliver="emu", order=order, gap_us=(0, 50, 300)[s % 3], epoch=s + 1)
