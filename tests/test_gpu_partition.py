@@ -56,3 +56,40 @@ def test_partition_create_rejects_bad_sizes():
     for bad in (0, 4, 20, 256, 1024):
         with pytest.raises(pk.PkError):
             pk.pk_partition_create(bad)
+
+
+def test_search_for_the_compute_unit_split():
+    """The split search runs a live AG+GEMM iteration per candidate and returns the fastest; every iteration's result
+    stays bit-identical to the pre-landed one."""
+    from paper_2511_13940_amd import tune
+    c = wl.CONFIGS["cfg2"]
+    rank = 1
+    inp = wl.ag_gemm_inputs(c.P, c.M, c.N, c.K, c.dtype, rank, seed=6)
+    base = hz.run_ag_gemm(c.P, rank, c.M, c.N, c.K, c.dtype, inp["chunks"], inp["B_local"])
+    full = np.concatenate(inp["chunks"], axis=0)
+    staging = hz.elem_view(full, "bf16")
+    A = staging.clone()
+    B = hz.elem_view(inp["B_local"], "bf16")
+    C = torch.zeros((c.M, c.N // c.P), dtype=torch.int16, device="cuda")
+    flags = torch.zeros(c.P, dtype=torch.int32, device="cuda")
+    counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
+    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    epoch = [0]
+    done = torch.cuda.Event()
+
+    def launch(comp, comm, cc):
+        epoch[0] += 1
+        done.record(comp)
+        comm.wait_event(done)
+        with torch.cuda.stream(comm):
+            counters.zero_()
+        pk.pk_emu_deliver_chunks(c.P, c.M, c.K, 2, staging, A, flags, epoch[0], inp["order"], 0, counters, stream=comm,
+                                 n_wg=4 * cc)
+        pk.pk_ag_gemm(c.P, rank, c.M, c.N, c.K, c.dtype, A, B, None, None, flags, epoch[0], C, status, stream=comp,
+                      comm_cus=cc)
+        comp.wait_stream(comm)
+
+    best, times = tune.search_comm_cus(launch, candidates=(8, 32, 64), iters=3, warmup=1)
+    assert best in times and set(times) == {8, 32, 64} and all(t > 0 for t in times.values())
+    assert status[0].item() == 0
+    assert np.array_equal(hz.bits_of(C), base["C_bits"])
