@@ -35,7 +35,10 @@
  *     to status[0..3] (first error wins) and drain; the host reads it after synchronising the stream.
  *     phase 1: a GEMM waiting for a chunk of A (index = chunk); phase 2: the reduce waiting for a tile's partials
  *     (index = tile); phase 3: pk_gemm_ar's closing wait (index = flag).
- *     timeout_us = 0 selects the default (2 s).  The caller zeroes `status` (4 x uint32) before the call.
+ *     timeout_us = 0 selects the default (2 s).  The caller zeroes `status` (PK_STATUS_WORDS x uint32) before the call.
+ *   - status[4..7] receive a timing report from workgroup 0 of the call's GEMM kernel: [4] ticks of the 100 MHz
+ *     wall clock and [5] core-clock cycles from its start to its end ([5] / [4] x 100 MHz = the clock the chip
+ *     held), [6] core-clock cycles inside its main loops, [7] the number of tiles it computed.
  */
 #ifndef PK_H
 #define PK_H
@@ -60,6 +63,8 @@ typedef enum {
 } pk_status;
 
 typedef enum { PK_BF16 = 0, PK_FP8_E4M3 = 1 } pk_dtype;
+
+#define PK_STATUS_WORDS 8    /* size of every `status` buffer, in uint32 */
 
 /* element type of the partial slots of pk_gemm_rs / pk_gemm_ar (`partials`, `outgoing`) */
 typedef enum {

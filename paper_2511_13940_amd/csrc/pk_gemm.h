@@ -224,6 +224,11 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     };
 
     // chunks of A known to have landed (the own one, and those this workgroup has waited for): EPI_AG, EPI_AGK
+    // workgroup 0 reports how long it ran, in ticks of the 100 MHz wall clock and in core-clock cycles, and how many of
+    // those cycles its main loops took: status[4..7] (the ratio of the first two is the clock the chip held)
+    const uint64_t t_wall0 = wall_clock64(), t_core0 = clock64();
+    uint64_t t_loops = 0;
+    uint32_t n_tiles_done = 0;
     uint64_t seen_chunks = 1ull << (g.rank & 63);
     const uint64_t all_chunks = g.k_chunks >= 64 ? ~0ull : (1ull << g.k_chunks) - 1;
     int v = blockIdx.x;
@@ -574,6 +579,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                 ktile(kt + 1, F{}, F{}, O{});
             }
         };
+        const uint64_t t_loop0 = clock64();
         run_ktiles(seg_ktiles);
         if (by_chunk) {
             // the other column chunks of A, in ring order from the own one; the first tile that touches a chunk waits for
@@ -606,6 +612,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             }
         }
 
+        t_loops += clock64() - t_loop0;
+        ++n_tiles_done;
         p_q = q;
         p_flag = flag;
         p_row0 = row0;
@@ -621,6 +629,12 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             __syncthreads();
             signal_prev();
         }
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        g.status[4] = (uint32_t)(wall_clock64() - t_wall0);
+        g.status[5] = (uint32_t)(clock64() - t_core0);
+        g.status[6] = (uint32_t)t_loops;
+        g.status[7] = n_tiles_done;
     }
 }
 

@@ -89,7 +89,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
     outgoing = slot_poison(P, mp, ncols, s16)
     flags_in = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     peers = [q for q in range(P) if q != rank]
     if order is None:
         order = peers
@@ -141,7 +141,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
     sa, sb = scale_t(scale_a), scale_t(scale_b)
     C = torch.full((M, N // P), -1, dtype=torch.int16, device="cuda")
     flags = torch.zeros(P, dtype=torch.int32, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     peers = [q for q in range(P) if q != rank]
     if order is None:
         order = [(rank + d) % P for d in range(1, P)]
@@ -197,7 +197,7 @@ def run_gemm_ar(P, rank, M, N, K, dtype, A_bits, B_bits, partials, peer_rows, sc
     flags_out = torch.zeros((P, fps), dtype=torch.int32, device="cuda")
     ar_in = torch.zeros((P, afps), dtype=torch.int32, device="cuda")
     ar_out = torch.zeros((P, afps), dtype=torch.int32, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     peers = [q for q in range(P) if q != rank]
     if order is None:
         order = peers
@@ -252,7 +252,7 @@ def run_ag_gemm_k(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b
     sa, sb = scale_t(scale_a), scale_t(scale_b)
     C = torch.full((M, N // P), -1, dtype=torch.int16, device="cuda")
     flags = torch.zeros(P, dtype=torch.int32, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     peers = [q for q in range(P) if q != rank]
     if order is None:
         order = [(rank + d) % P for d in range(1, P)]

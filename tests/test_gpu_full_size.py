@@ -116,7 +116,7 @@ def test_gemm_rs_at_the_papers_table3_size_sampled_rows():
     flags_in[rank].zero_()
     flags_out = torch.zeros_like(flags_in)
     out = torch.full((mp, MN), -1, dtype=torch.int16, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     pk.pk_gemm_rs(P, rank, MN, MN, P * kl, "bf16", A, B, None, None, part, outgoing, flags_in, flags_out, 3, out,
                   pk.PHASE_ALL, status)
     torch.cuda.synchronize()

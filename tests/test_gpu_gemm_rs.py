@@ -155,7 +155,7 @@ def test_epoch_reuse_without_reset():
     outgoing = torch.zeros((P, mp, N), dtype=torch.float32, device="cuda")
     flags_in = torch.zeros((P, plan.flags_per_slot), dtype=torch.int32, device="cuda")
     flags_out = torch.zeros_like(flags_in)
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     out = torch.zeros((mp, N), dtype=torch.int16, device="cuda")
     for e in [1, 2, 3, 0x7FFFFFFF, 0x80000000, 0x80000001, 0xFFFFFFFF, 0, 1]:
         signed = e if e < 2 ** 31 else e - 2 ** 32
@@ -199,7 +199,7 @@ def test_reduce_phase_alone_matches_closed_forms():
     part = hz.dev(partials)
     out = torch.zeros((mp, N), dtype=torch.int16, device="cuda")
     flags = torch.full((P, plan.flags_per_slot), 4, dtype=torch.int32, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     pk.pk_gemm_rs(P, rank, M, N, K, "bf16", None, None, None, None, part, None, flags, None, 4, out,
                   pk.PHASE_REDUCE, status)
     torch.cuda.synchronize()

@@ -27,7 +27,7 @@ def test_captured_mlp_block_replays_bit_identically():
     chunk_flags = torch.full((P,), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
     H = torch.zeros((M, I // P), dtype=torch.int16, device="cuda")
     out = torch.zeros((mp, D), dtype=torch.int16, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
 
     def block(epoch):
         pk.pk_ag_gemm(P, rank, M, I, D, "bf16", X, W1, None, None, chunk_flags, epoch, H, status, act="silu")

@@ -73,7 +73,7 @@ def test_search_for_the_compute_unit_split():
     C = torch.zeros((c.M, c.N // c.P), dtype=torch.int16, device="cuda")
     flags = torch.zeros(c.P, dtype=torch.int32, device="cuda")
     counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
-    status = torch.zeros(4, dtype=torch.int32, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
     epoch = [0]
     done = torch.cuda.Event()
 
