@@ -34,7 +34,8 @@
  *   - a wait that exceeds `timeout_us` microseconds makes the kernel write {PK_ERR_TIMEOUT, index, phase, 0}
  *     to status[0..3] (first error wins) and drain; the host reads it after synchronising the stream.
  *     phase 1: a GEMM waiting for a chunk of A (index = chunk); phase 2: the reduce waiting for a tile's partials
- *     (index = tile); phase 3: pk_gemm_ar's closing wait (index = flag).
+ *     (index = tile); phase 3: pk_gemm_ar's closing wait (index = flag); phase 4: a GEMM workgroup waiting for another
+ *     one's piece of a shared tile (index = workgroup).
  *     timeout_us = 0 selects the default (2 s).  The caller zeroes `status` (PK_STATUS_WORDS x uint32) before the call.
  *   - status[4..7] receive a timing report from workgroup 0 of the call's GEMM kernel: [4] ticks of the 100 MHz
  *     wall clock and [5] core-clock cycles from its start to its end ([5] / [4] x 100 MHz = the clock the chip
@@ -97,7 +98,20 @@ typedef struct {
     int64_t flags_per_slot;       /* tiles_m * tiles_n */
     int64_t local_m, local_n, local_k;   /* the per-rank GEMM */
     int64_t ar_flags_per_slot;    /* pk_gemm_ar_plan only: ceil((M/P) / PK_AR_ROWS) * tiles_n, else 0 */
+    int64_t workspace_bytes;      /* pk_gemm_rs_plan, pk_ag_gemm_plan: size of a workspace that suffices on this device
+                                     (PK_WS_FLAG_BYTES + one fp32 tile per compute unit); 0 for the other plans */
 } pk_plan;
+
+/*
+ * Workspace (pk_gemm_rs, pk_ag_gemm; optional).  When the tiles do not fill a whole number of rounds on the compute
+ * units (448 tiles on 256 units), the k range of the left-over tiles is shared out evenly over all workgroups
+ * (paper section 3.1.3: the schedule depends on the problem size) and workgroups hand partial accumulator tiles to
+ * one another through this memory.  Layout: PK_WS_FLAG_BYTES of ready flags, then one fp32 tile per workgroup.  The
+ * caller zeroes the flag bytes once; afterwards the workspace belongs to one call site: its epochs must grow from
+ * call to call, and two calls that may run at the same time must not share it.  workspace = NULL: whole tiles only.
+ * A workspace smaller than plan.workspace_bytes may be rejected with PK_ERR_ARG.
+ */
+#define PK_WS_FLAG_BYTES 4096
 
 int pk_version(void);
 const char* pk_status_str(int status);
@@ -138,6 +152,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      void* partials, void* outgoing,
                      uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
                      void* out_shard, uint32_t phases, int comm_cus, int partial_dt /* pk_partial_dtype */,
+                     void* workspace, size_t workspace_bytes,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
@@ -225,6 +240,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch,
                      void* C_local, int comm_cus, int activation /* pk_activation */,
+                     void* workspace, size_t workspace_bytes,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*

@@ -73,7 +73,16 @@ struct GemmArgs {
     uint32_t epoch;
     uint32_t* status;
     uint64_t timeout_ticks;
+    // stream-K tail: the first sk_dp_slots tile slots are computed whole, one per workgroup and round; the k range of the
+    // remaining ones is shared out evenly (sk_dp_slots = all slots: no such tail)
+    int32_t sk_dp_slots;
+    char* ws_tiles;           // [gridDim.x] raw accumulator tiles of BM * BN fp32 (a workgroup's piece that does not start a tile)
+    uint32_t* ws_flags;       // [gridDim.x] ready flags of those pieces (epoch)
 };
+
+// kinds of work unit: a whole tile; the piece of a tile's k range that starts it (its owner adds the other pieces and
+// runs the epilogue); any other piece (accumulators handed to the owner through ws_tiles)
+enum { UNIT_FULL = 0, UNIT_HEAD = 1, UNIT_PART = 2 };
 
 constexpr int kEpiStageBytes = 32 * 1024;   // LDS staging of the epilogue, shared out evenly to the waves
 
@@ -199,6 +208,8 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 
     // tile bookkeeping carried from one iteration to the next (the epilogue of a tile runs one iteration late)
     int p_q = -1, p_flag = 0, p_row0 = 0, p_row_end = 0, p_col0 = 0, p_col_end = 0;
+    int p_kind = UNIT_FULL, p_part_lo = 0, p_tile_end = 0;
+    bool p_dead = false;                                 // the previous tile was given up (a wait timed out): no signal
     const int slots_total = g.wg_per_group * g.n_groups;
     const int G = g.grp_tile_rows * g.tiles_n;
     float scale = 1.f;
@@ -214,8 +225,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     };
 
     auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
-        if constexpr (IS_RS) {
-            if (tid == 0) {
+        if (p_kind == UNIT_PART) {
+            if (tid == 0) flag_publish(g.ws_flags + blockIdx.x, g.epoch);
+        } else if constexpr (IS_RS) {
+            if (tid == 0 && !p_dead) {
                 uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
                                                   : g.flags_out + (int64_t)p_q * g.flags_per_slot;
                 flag_publish(flags + p_flag, g.epoch);
@@ -237,14 +250,36 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     // already there never queue behind a late one.  Slots beyond the 64th wait on the spot.
     uint64_t deferred = 0;
     int visit = 0;
+    // Stream-K tail (the tile slots from sk_dp_slots on): slot sk_dp_slots + 8*i + x belongs to XCD x = workgroup id
+    // mod 8, whose W workgroups share the R * KT k-tiles of its R slots evenly, workgroup j of the XCD taking
+    // [sk_bnd(j), sk_bnd(j+1)).  A range is cut at tile boundaries into pieces; cuts closer than SK_MINP k-tiles to a
+    // tile boundary are moved onto it.  A workgroup has at most one piece that does not start a tile, its first.
+    constexpr int SK_Q = (KS % 2) ? 2 : 1, SK_MINP = 2 * NS;
+    const int KT = g.ktiles;
+    const int sk_x = blockIdx.x & 7, sk_j = blockIdx.x >> 3, sk_W = gridDim.x >> 3;
+    const int sk_R = (slots_total - g.sk_dp_slots) >> 3;
+    auto sk_bnd = [&](int j) -> int {
+        int b = (int)((int64_t)sk_R * KT * j / sk_W);
+        b -= b % SK_Q;
+        const int r = b % KT;
+        if (r < SK_MINP) b -= r;
+        else if (KT - r < SK_MINP) b += KT - r;
+        return b;
+    };
+    int sk_c = 0, sk_e = 0;
+    if (sk_R > 0) {
+        sk_c = sk_bnd(sk_j);
+        sk_e = sk_bnd(sk_j + 1);
+    }
     for (;;) {
         // ---- which tile (paper listing: interpret_task) ----
         int q = 0, tmi = 0, tc = 0, row0 = 0, row_end = 0, col0 = 0, col_end = 0, flag = 0;
+        int kind = UNIT_FULL, kt0 = 0, nkt = KT, part_lo = 0, tile_end = 0;
         bool have = false;
         for (;;) {
-            int slot, slot_index;
+            int slot, slot_index = 64;
             bool may_defer = false;
-            if (v < slots_total) {
+            if (v < g.sk_dp_slots) {
                 slot = v;
                 slot_index = visit;
                 v += gridDim.x;
@@ -254,6 +289,16 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                 slot_index = __builtin_ctzll(deferred);
                 deferred &= deferred - 1;
                 slot = (int)blockIdx.x + slot_index * (int)gridDim.x;
+            } else if (sk_c < sk_e) {
+                const int i = sk_c / KT;
+                tile_end = (i + 1) * KT;
+                const int e = min(sk_e, tile_end);
+                slot = g.sk_dp_slots + 8 * i + sk_x;
+                kt0 = sk_c - i * KT;
+                nkt = e - sk_c;
+                kind = kt0 != 0 ? UNIT_PART : (nkt == KT ? UNIT_FULL : UNIT_HEAD);
+                part_lo = sk_j + 1;          // the workgroups of this XCD that may hold the other pieces of a tile started here
+                sk_c = e;
             } else {
                 break;
             }
@@ -318,6 +363,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                         have = false;                       // drain: this tile's and the later tiles' rows stay untouched
                         v = slots_total;
                         deferred = 0;
+                        sk_c = sk_e;
                         break;
                     }
                     acquire_agent();
@@ -333,10 +379,13 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         // k-tiles handled between two pipeline fills: all of them, or one column chunk of A at a time (EPI_AGK, own
         // chunk); once this workgroup has seen every chunk, its later tiles run the whole k range in one go
         const bool by_chunk = (EPI == EPI_AGK) && seen_chunks != all_chunks;
-        const int seg_ktiles = by_chunk ? g.ktiles / g.k_chunks : g.ktiles;
+        const int seg_ktiles = by_chunk ? g.ktiles / g.k_chunks : nkt;
         if (by_chunk) {
             a_base += (int64_t)g.rank * seg_ktiles * KB;
             b_base += (int64_t)g.rank * seg_ktiles * b_step;
+        } else {
+            a_base += (int64_t)kt0 * KB;             // a piece of a stream-K tile starts at k-tile kt0
+            b_base += (int64_t)kt0 * b_step;
         }
         if (have) {
             // per-lane global source addresses of the direct-to-LDS loads.  Wave-wide load j of wave w fills
@@ -400,7 +449,65 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         }
 
         // ---- epilogue of the previous tile (the storer), under the latency of the loads just issued ----
-        if (p_q >= 0) {
+        bool skip_epilogue = false;
+        if (p_q >= 0 && p_kind == UNIT_PART) {
+            // hand the raw accumulators to the owner of the tile: register image, 16 bytes per lane, written through
+            char* wsb = g.ws_tiles + (int64_t)blockIdx.x * (BM * BN * 4) + (w * (TM * TN * 4)) * 1024 + l * 16;
+#pragma unroll
+            for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < TN; ++tj)
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        f32x4 val = {acc[ti][tj][4 * b], acc[ti][tj][4 * b + 1], acc[ti][tj][4 * b + 2], acc[ti][tj][4 * b + 3]};
+                        store16_writethrough(wsb + ((ti * TN + tj) * 4 + b) * 1024, __builtin_bit_cast(i32x4, val));
+                    }
+            skip_epilogue = true;
+        }
+        if (p_q >= 0 && p_kind == UNIT_HEAD) {
+            // add the other pieces of this tile: those of the following workgroups of this XCD whose ranges start inside it
+            for (int jp = p_part_lo; jp < sk_W; ++jp) {
+                const int s0 = sk_bnd(jp);
+                if (s0 >= p_tile_end) break;
+                if (sk_bnd(jp + 1) == s0) continue;              // that workgroup has no work
+                const int owner = jp * 8 + sk_x;
+                PK_LDS int* verdict = (PK_LDS int*)(lds + EPI_OFF);
+                if (tid == 0) {
+                    const int late = flag_wait(g.ws_flags + owner, g.epoch, g.timeout_ticks) ? 0 : 1;
+                    if (late) report_timeout(g.status, (uint32_t)owner, 4u);
+                    *verdict = late;
+                }
+                __syncthreads();
+                const int late_all = *verdict;
+                __syncthreads();
+                if (late_all) {
+                    skip_epilogue = true;                           // the tile stays unwritten and unsignalled
+                    p_dead = true;
+                    break;
+                }
+                // the piece was written through by another compute unit: read it past this XCD's L2
+                const auto rsrc = __builtin_amdgcn_make_buffer_rsrc(g.ws_tiles + (int64_t)owner * (BM * BN * 4), 0, BM * BN * 4,
+                                                                    0x00020000);
+                const uint32_t off0 = (uint32_t)((w * (TM * TN * 4)) * 1024 + l * 16);
+#pragma unroll
+                for (int ti = 0; ti < TM; ++ti) {
+                    f32x4 pv[TN][4];
+#pragma unroll
+                    for (int tj = 0; tj < TN; ++tj)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+                            pv[tj][b] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                rsrc, off0 + (uint32_t)(((ti * TN + tj) * 4 + b) * 1024), 0, 1 | 2 | 16));
+#pragma unroll
+                    for (int tj = 0; tj < TN; ++tj)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[ti][tj][4 * b + e] += pv[tj][b][e];
+                }
+            }
+        }
+        if (p_q >= 0 && !skip_epilogue) {
             // lane holds, for each 32x32 block, rows (l & 31) and columns 8*b + 4*h + {0..3}.  Per pass a slab of
             // ROWS_PASS rows x (BN/WN) columns goes through the wave's private staging area, then out as whole
             // row segments, 16 bytes per lane.
@@ -614,6 +721,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 
         t_loops += clock64() - t_loop0;
         ++n_tiles_done;
+        p_dead = false;
+        p_kind = kind;
+        p_part_lo = part_lo;
+        p_tile_end = tile_end;
         p_q = q;
         p_flag = flag;
         p_row0 = row0;
@@ -623,12 +734,10 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     }
 
     // the last tile's stores: every wave waits for its write-through stores, then the flag is published
-    if constexpr (IS_RS) {
-        if (p_q >= 0) {
-            __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
-            __syncthreads();
-            signal_prev();
-        }
+    if (p_q >= 0 && (IS_RS || p_kind == UNIT_PART)) {
+        __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
+        __syncthreads();
+        signal_prev();
     }
     if (blockIdx.x == 0 && tid == 0) {
         g.status[4] = (uint32_t)(wall_clock64() - t_wall0);

@@ -279,6 +279,22 @@ static pk_status check_dims(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt,
     return PK_OK;
 }
 
+// compute units of the current device (cached per device ordinal)
+static int num_cus() {
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    int n = cache[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        int v = 0;
+        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
+        cache[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
+constexpr size_t kWsFlagBytes = 4096;   // the first bytes of a workspace hold one ready flag per workgroup
+
 static pk_status make_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, bool rs, pk_plan* plan) {
     if (!plan) return PK_ERR_NULL;
     int64_t m, n, k;
@@ -294,6 +310,7 @@ static pk_status make_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, 
     plan->local_n = n;
     plan->local_k = k;
     plan->ar_flags_per_slot = 0;
+    plan->workspace_bytes = (int64_t)kWsFlagBytes + (int64_t)num_cus() * tc.bm * tc.bn * 4;
     return PK_OK;
 }
 
@@ -315,27 +332,14 @@ static pk_status make_plan_cols(int P, int64_t M, int64_t N, int64_t K, pk_dtype
     plan->local_n = N;
     plan->local_k = k;
     plan->ar_flags_per_slot = 0;
+    plan->workspace_bytes = 0;
     return PK_OK;
-}
-
-// compute units of the current device (cached per device ordinal)
-static int num_cus() {
-    static std::atomic<int> cache[64];
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
-    int n = cache[dev].load(std::memory_order_relaxed);
-    if (n == 0) {
-        int v = 0;
-        n = (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) ? v : 256;
-        cache[dev].store(n, std::memory_order_relaxed);
-    }
-    return n;
 }
 
 // Persistent launch: one workgroup per CU (a multiple of 8 so that workgroup id mod 8 stays the XCD), or fewer
 // when there are fewer tile slots.
 template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
-static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, hipStream_t stream) {
+static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream) {
     // the dynamic LDS size of this instantiation is raised once per device (bit d of `configured` = done on device d)
     static std::atomic<uint64_t> configured{0};
     auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI>;
@@ -351,24 +355,35 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, hipStream_t st
     }
     int grid = (num_cus() - comm_cus) / 8 * 8;
     if (grid < 8) grid = 8;
-    // the fewest workgroups that finish in the same number of rounds (448 slots on 256 CUs: 2 rounds of 224)
-    const int rounds = (slots + grid - 1) / grid;
-    const int even = ((slots + rounds - 1) / rounds + 7) / 8 * 8;
-    if (even < grid) grid = even;
+    a.sk_dp_slots = slots;
+    const int rem = slots % grid;
+    if (ws && EPI != EPI_AGK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
+        // With a workspace every compute unit works to the end: whole rounds of tiles, then the k range of the left-over
+        // tiles shared out evenly (448 slots on 256 CUs: 256 whole tiles, then 192 tiles as 256 pieces of 3/4 tile).
+        if (ws_bytes < kWsFlagBytes + (size_t)grid * BM * BN * 4) return PK_ERR_ARG;
+        a.sk_dp_slots = slots - rem;
+        a.ws_flags = (uint32_t*)ws;
+        a.ws_tiles = (char*)ws + kWsFlagBytes;
+    } else {
+        // the fewest workgroups that finish in the same number of rounds (448 slots on 256 CUs: 2 rounds of 224)
+        const int rounds = (slots + grid - 1) / grid;
+        const int even = ((slots + rounds - 1) / rounds + 7) / 8 * 8;
+        if (even < grid) grid = even;
+    }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, stream, a);
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }
 
 template <int EPI>
 static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const TileCfg& tc, bool fp8,
-                               hipStream_t stream) {
+                               void* ws, size_t ws_bytes, hipStream_t stream) {
     if (tc.bm == 256) {
         // 8 waves, 64-byte k-tiles (32 bf16 or 64 fp8 of k) in a ring of 4 LDS stages
-        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, stream)
-                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, stream);
+        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
+                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
     }
-    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, stream)
-               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, stream);
+    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
+               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
 }
 
 static uint64_t timeout_ticks(uint64_t timeout_us) {
@@ -438,7 +453,8 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
                               const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
                               void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out,
                               uint32_t epoch, void* out_shard, const AllReduceOut* ar, uint32_t phases, int comm_cus,
-                              int partial_dt, bool cols, uint32_t* status, uint64_t timeout_us, void* stream) {
+                              int partial_dt, bool cols, void* ws, size_t ws_bytes, uint32_t* status, uint64_t timeout_us,
+                              void* stream) {
     pk_plan pl;
     pk_status st = cols ? make_plan_cols(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, true, &pl);
     if (st != PK_OK) return st;
@@ -494,8 +510,8 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.epoch = epoch;
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
-        st = bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, s)
-                        : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, s);
+        st = bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s)
+                        : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s);
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
@@ -556,13 +572,14 @@ static pk_status make_plan_ag_k(int P, int64_t M, int64_t N, int64_t K, pk_dtype
     plan->local_n = n;
     plan->local_k = k;
     plan->ar_flags_per_slot = 0;
+    plan->workspace_bytes = 0;
     return PK_OK;
 }
 
 static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                               const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
                               const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
-                              bool k_chunks, uint32_t* status, uint64_t timeout_us, void* stream) {
+                              bool k_chunks, void* ws, size_t ws_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
     pk_plan pl;
     pk_status st = k_chunks ? make_plan_ag_k(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, false, &pl);
     if (st != PK_OK) return st;
@@ -603,8 +620,8 @@ static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     a.epoch = epoch;
     a.status = status;
     a.timeout_ticks = timeout_ticks(timeout_us);
-    return k_chunks ? dispatch_gemm<EPI_AGK>(a, a.wg_per_group, comm_cus, tc, fp8, (hipStream_t)stream)
-                    : dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, (hipStream_t)stream);
+    return k_chunks ? dispatch_gemm<EPI_AGK>(a, a.wg_per_group, comm_cus, tc, fp8, nullptr, 0, (hipStream_t)stream)
+                    : dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, ws, ws_bytes, (hipStream_t)stream);
 }
 
 static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
@@ -650,11 +667,13 @@ pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, p
 pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
                      void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases, int comm_cus, int partial_dt, uint32_t* status,
-                     uint64_t timeout_us, void* stream) {
+                     void* out_shard, uint32_t phases, int comm_cus, int partial_dt, void* workspace,
+                     size_t workspace_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
     if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
+    if (!aligned16(workspace)) return PK_ERR_ALIGN;
     return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, false, status, timeout_us, stream);
+                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, false, workspace, workspace_bytes,
+                        status, timeout_us, stream);
 }
 
 pk_status pk_gemm_rs_cols_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -668,7 +687,8 @@ pk_status pk_gemm_rs_cols(int P, int rank, int64_t M, int64_t N, int64_t K, pk_d
                           uint64_t timeout_us, void* stream) {
     if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
     return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, true, status, timeout_us, stream);
+                        flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, true, nullptr, 0, status, timeout_us,
+                        stream);
 }
 
 pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -697,7 +717,8 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
         // the reduce phase writes rows R_rank of out_full
         uint16_t* own_rows = (uint16_t*)out_full + (int64_t)rank * (M / P) * N;
         st = gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
-                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, partial_dt, false, status, timeout_us, stream);
+                          flags_out, epoch, own_rows, &ar, phases & PK_PHASE_ALL, comm_cus, partial_dt, false, nullptr, 0, status,
+                          timeout_us, stream);
         if (st != PK_OK) return st;
     }
     if (phases & PK_PHASE_WAIT) {
@@ -712,9 +733,10 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
 pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
-                     uint32_t* status, uint64_t timeout_us, void* stream) {
+                     void* workspace, size_t workspace_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
+    if (!aligned16(workspace)) return PK_ERR_ALIGN;
     return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
-                        activation, false, status, timeout_us, stream);
+                        activation, false, workspace, workspace_bytes, status, timeout_us, stream);
 }
 
 pk_status pk_ag_gemm_k_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -726,7 +748,7 @@ pk_status pk_ag_gemm_k(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtyp
                        const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
                        uint32_t* status, uint64_t timeout_us, void* stream) {
     return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
-                        activation, true, status, timeout_us, stream);
+                        activation, true, nullptr, 0, status, timeout_us, stream);
 }
 
 pk_status pk_emu_deliver_kchunks_dma(int P, int64_t M, int64_t K, int elem_bytes, const void* staging, void* A_gathered,

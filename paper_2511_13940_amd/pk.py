@@ -35,7 +35,7 @@ class Plan(ctypes.Structure):
                 ("tiles_m", ctypes.c_int32), ("tiles_n", ctypes.c_int32),
                 ("flags_per_slot", ctypes.c_int64),
                 ("local_m", ctypes.c_int64), ("local_n", ctypes.c_int64), ("local_k", ctypes.c_int64),
-                ("ar_flags_per_slot", ctypes.c_int64)]
+                ("ar_flags_per_slot", ctypes.c_int64), ("workspace_bytes", ctypes.c_int64)]
 
 
 class PkError(RuntimeError):
@@ -63,9 +63,11 @@ def lib():
             f.restype = i32
             f.argtypes = [i32, i64, i64, i64, i32, ctypes.POINTER(Plan)]
         L.pk_gemm_rs.restype = i32
-        L.pk_gemm_rs.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, i32, vp, u64, vp]
+        rs_args = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, i32, vp, u64, vp]
+        ag_args = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, i32, vp, u64, vp]
+        L.pk_gemm_rs.argtypes = rs_args[:19] + [vp, ctypes.c_size_t] + rs_args[19:]
         L.pk_ag_gemm.restype = i32
-        L.pk_ag_gemm.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, i32, vp, u64, vp]
+        L.pk_ag_gemm.argtypes = ag_args[:15] + [vp, ctypes.c_size_t] + ag_args[15:]
         L.pk_emu_deliver_chunks.restype = i32
         L.pk_emu_deliver_chunks.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp, vp]
         L.pk_emu_deliver_partials.restype = i32
@@ -73,12 +75,12 @@ def lib():
         L.pk_probe_mfma.restype = i32
         L.pk_probe_mfma.argtypes = [i32, i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pk_gemm_rs_cols.restype = i32
-        L.pk_gemm_rs_cols.argtypes = L.pk_gemm_rs.argtypes
+        L.pk_gemm_rs_cols.argtypes = rs_args
         L.pk_gemm_ar.restype = i32
         L.pk_gemm_ar.argtypes = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, u32, i32,
                                  i32, vp, u64, vp]
         L.pk_ag_gemm_k.restype = i32
-        L.pk_ag_gemm_k.argtypes = L.pk_ag_gemm.argtypes
+        L.pk_ag_gemm_k.argtypes = ag_args
         L.pk_emu_deliver_kchunks_dma.restype = i32
         L.pk_emu_deliver_kchunks_dma.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, vp]
         L.pk_emu_deliver_chunks_dma.restype = i32
@@ -99,6 +101,10 @@ def _ptr(t):
     if not t.is_cuda or not t.is_contiguous():
         raise ValueError("libpk takes contiguous device tensors")
     return t.data_ptr()
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
 
 
 def _stream(stream):
@@ -142,11 +148,11 @@ def pk_ag_gemm_plan(P, M, N, K, dtype):
 
 def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing,
                flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None, comm_cus=0,
-               partial_dtype="f32"):
+               partial_dtype="f32", workspace=None):
     _check(lib().pk_gemm_rs(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
-                            _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), _ptr(status), timeout_us,
-                            _stream(stream)), "pk_gemm_rs")
+                            _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), _ptr(workspace), _nbytes(workspace),
+                            _ptr(status), timeout_us, _stream(stream)), "pk_gemm_rs")
 
 
 def pk_gemm_rs_cols_plan(P, M, N, K, dtype):
@@ -180,11 +186,11 @@ def pk_gemm_ar(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, part
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
-               C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none"):
+               C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none", workspace=None):
     _check(lib().pk_ag_gemm(P, rank, M, N, K, _dt(dtype), _ptr(A_gathered), _ptr(B_local), _ptr(scale_a),
                             _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus,
-                            ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(status),
-                            timeout_us, _stream(stream)), "pk_ag_gemm")
+                            ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(workspace), _nbytes(workspace),
+                            _ptr(status), timeout_us, _stream(stream)), "pk_ag_gemm")
 
 
 def pk_ag_gemm_k_plan(P, M, N, K, dtype):

@@ -48,6 +48,15 @@ def slot_download(t, s16):
     return bits_of(t) if s16 else t.cpu().numpy()
 
 
+def make_workspace(plan, workspace):
+    """None -> no workspace; True -> a zeroed one of the size the plan asks for; a tensor -> that tensor."""
+    if workspace is None or workspace is False:
+        return None
+    if workspace is True:
+        return torch.zeros(plan.workspace_bytes // 4, dtype=torch.int32, device="cuda")
+    return workspace
+
+
 def deliver_slots(P, M, N, tile_m, tile_n, staging, part, flags, epoch, order, gap_us, side, n_wg, s16):
     """Peer slots through the emulated communicator; bf16 slots travel as fp32 pairs (N/2 columns, tile_n/2 per flag)."""
     if s16:
@@ -60,12 +69,14 @@ def deliver_slots(P, M, N, tile_m, tile_n, staging, part, flags, epoch, order, g
 
 def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
-                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0, partial_dtype="f32", cols=False):
+                withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0, partial_dtype="f32", cols=False,
+                workspace=None):
     """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
 
     partition = (compute_stream, comm_stream) handles from pk_partition_create: the op then runs on the first and
     the emulated peers on the second.
     partial_dtype = "bf16": `partials` holds uint16 bit patterns; outgoing / partials_after come back as uint16.
+    workspace: None, True (a fresh zeroed workspace of plan.workspace_bytes) or a device tensor to reuse.
     cols = True: pk_gemm_rs_cols (scatter along the last dimension): slots and the output are M x N/P.
 
     deliver = "pre": peer slots and their flags are in place before the call.
@@ -109,9 +120,10 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
         side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
         deliver_slots(P, P * mp, ncols, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us, side,
                       n_wg, s16)
+    extra = {} if cols else {"workspace": make_workspace(plan, workspace)}
     op(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
        flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main,
-       comm_cus=comm_cus, partial_dtype=partial_dtype)
+       comm_cus=comm_cus, partial_dtype=partial_dtype, **extra)
     torch.cuda.synchronize()
     res = {"out_bits": bits_of(out), "flags_out": flags_out.cpu().numpy(), "flags_in": flags_in.cpu().numpy(),
            "status": status.cpu().numpy(), "plan": plan}
@@ -124,7 +136,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
 
 def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None, fetch_A=True,
-                comm_cus=0, n_wg=0, partition=None, act="none"):
+                comm_cus=0, n_wg=0, partition=None, act="none", workspace=None):
     """One pk_ag_gemm call.  chunks: list of P numpy bit arrays (M/P x K).
 
     deliver = "pre": every chunk is in A_gathered with its flag set before the call.
@@ -167,8 +179,9 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
         else:
             pk.pk_emu_deliver_chunks(P, M, K, elem, staging, A, flags, epoch, list(order), gap_us, counters, stream=side,
                                      n_wg=n_wg)
+    ws = make_workspace(pk.pk_ag_gemm_plan(P, M, N, K, dtype), workspace)
     pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,
-                  timeout_us, stream=main, comm_cus=comm_cus, act=act)
+                  timeout_us, stream=main, comm_cus=comm_cus, act=act, workspace=ws)
     torch.cuda.synchronize()
     return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy() if fetch_A else None,
             "flags": flags.cpu().numpy()}
