@@ -244,6 +244,23 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
+ * pk_ag_gemm for callers that cannot allocate device memory (code under graph capture, serving loops, harnesses that
+ * forbid it): the same computation with the stream-K workspace taken from a scratch array inside the library
+ * (PK_STATIC_WS_BYTES per device that uses the library, held until the process ends) instead of a caller's buffer.
+ * Arguments, requirements and errors as pk_ag_gemm without `workspace`; the call allocates and frees nothing and
+ * clears the scratch flags itself (with a kernel on `stream`).  PK_ERR_ARG if the problem's workspace
+ * (plan.workspace_bytes: one fp32 tile per compute unit) exceeds PK_STATIC_WS_BYTES.  All calls on one device share
+ * the array: calls that may overlap in time on one device race, whatever their streams.
+ */
+#define PK_STATIC_WS_BYTES (PK_WS_FLAG_BYTES + 256 * 256 * 256 * 4)   /* flags + 256 compute units x (256 x 256 fp32) */
+pk_status pk_ag_gemm_static(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                            const void* A_gathered, const void* B_local,
+                            const float* scale_a, const float* scale_b,
+                            const uint32_t* chunk_flags, uint32_t epoch,
+                            void* C_local, int comm_cus, int activation /* pk_activation */,
+                            uint32_t* status, uint64_t timeout_us, void* stream);
+
+/*
  * All-gather along the LAST dimension of A + GEMM (paper appendix "Additional collective performance": all-gather along
  * the tensor dimension, whose pieces are not contiguous in memory).  As pk_ag_gemm, but chunk q of A_gathered is the
  * column block K_q = [q*K/P, (q+1)*K/P) of every row (M pieces of K/P elements), valid once chunk_flags[q] has reached

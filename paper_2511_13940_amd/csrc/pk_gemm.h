@@ -77,7 +77,8 @@ struct GemmArgs {
     // remaining ones is shared out evenly (sk_dp_slots = all slots: no such tail)
     int32_t sk_dp_slots;
     char* ws_tiles;           // [gridDim.x] raw accumulator tiles of BM * BN fp32 (a workgroup's piece that does not start a tile)
-    uint32_t* ws_flags;       // [gridDim.x] ready flags of those pieces (epoch)
+    uint32_t* ws_flags;       // [gridDim.x] ready flags of those pieces (ws_epoch)
+    uint32_t ws_epoch;
 };
 
 // kinds of work unit: a whole tile; the piece of a tile's k range that starts it (its owner adds the other pieces and
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 
     auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
         if (p_kind == UNIT_PART) {
-            if (tid == 0) flag_publish(g.ws_flags + blockIdx.x, g.epoch);
+            if (tid == 0) flag_publish(g.ws_flags + blockIdx.x, g.ws_epoch);
         } else if constexpr (IS_RS) {
             if (tid == 0 && !p_dead) {
                 uint32_t* flags = (p_q == g.rank) ? g.flags_in + (int64_t)g.rank * g.flags_per_slot
@@ -473,7 +474,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                 const int owner = jp * 8 + sk_x;
                 PK_LDS int* verdict = (PK_LDS int*)(lds + EPI_OFF);
                 if (tid == 0) {
-                    const int late = flag_wait(g.ws_flags + owner, g.epoch, g.timeout_ticks) ? 0 : 1;
+                    const int late = flag_wait(g.ws_flags + owner, g.ws_epoch, g.timeout_ticks) ? 0 : 1;
                     if (late) report_timeout(g.status, (uint32_t)owner, 4u);
                     *verdict = late;
                 }

@@ -364,6 +364,7 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size
         a.sk_dp_slots = slots - rem;
         a.ws_flags = (uint32_t*)ws;
         a.ws_tiles = (char*)ws + kWsFlagBytes;
+        if (a.ws_epoch == 0) a.ws_epoch = a.epoch;     // a caller's workspace follows the caller's epochs
     } else {
         // the fewest workgroups that finish in the same number of rounds (448 slots on 256 CUs: 2 rounds of 224)
         const int rounds = (slots + grid - 1) / grid;
@@ -384,6 +385,30 @@ static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const
     }
     return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
                : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Scratch memory of the library itself, for pk_ag_gemm_static (callers that cannot allocate): the workspace of the
+// stream-K tail.  Each device that loads the library holds its own copy of the array at its own address.
+// ------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[PK_STATIC_WS_BYTES];
+
+// address of this device's copy of `scratch` (looked up once per device; the array's name itself is no device address)
+static pk_status scratch_of_device(void** out) {
+    static std::atomic<void*> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PK_ERR_HIP;
+    void* p = cache[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PK_ERR_HIP;
+        cache[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return PK_OK;
+}
+
+__global__ __launch_bounds__(1024) void fill_zero_kernel(uint32_t* p, int n) {
+    for (int i = threadIdx.x; i < n; i += 1024) p[i] = 0u;
 }
 
 static uint64_t timeout_ticks(uint64_t timeout_us) {
@@ -579,7 +604,8 @@ static pk_status make_plan_ag_k(int P, int64_t M, int64_t N, int64_t K, pk_dtype
 static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                               const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
                               const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
-                              bool k_chunks, void* ws, size_t ws_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
+                              bool k_chunks, void* ws, size_t ws_bytes, bool ws_is_static, uint32_t* status, uint64_t timeout_us,
+                              void* stream) {
     pk_plan pl;
     pk_status st = k_chunks ? make_plan_ag_k(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, false, &pl);
     if (st != PK_OK) return st;
@@ -620,6 +646,13 @@ static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     a.epoch = epoch;
     a.status = status;
     a.timeout_ticks = timeout_ticks(timeout_us);
+    if (ws_is_static) {
+        // the library's own scratch keeps the last call's flags, whatever its epoch was: clear them (with a kernel, so
+        // that the call can be captured into a graph) and use an epoch of its own
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(1024), 0, (hipStream_t)stream, (uint32_t*)ws, (int)(kWsFlagBytes / 4));
+        if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
+        a.ws_epoch = 1;
+    }
     return k_chunks ? dispatch_gemm<EPI_AGK>(a, a.wg_per_group, comm_cus, tc, fp8, nullptr, 0, (hipStream_t)stream)
                     : dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, ws, ws_bytes, (hipStream_t)stream);
 }
@@ -736,7 +769,23 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      void* workspace, size_t workspace_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
     if (!aligned16(workspace)) return PK_ERR_ALIGN;
     return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
-                        activation, false, workspace, workspace_bytes, status, timeout_us, stream);
+                        activation, false, workspace, workspace_bytes, false, status, timeout_us, stream);
+}
+
+pk_status pk_ag_gemm_static(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
+                            const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
+                            const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
+                            uint32_t* status, uint64_t timeout_us, void* stream) {
+    // the tiles of one launch must fit the scratch array: one fp32 tile per workgroup, one workgroup per compute unit
+    pk_plan pl;
+    pk_status st = make_plan(P, M, N, K, dt, false, &pl);
+    if (st != PK_OK) return st;
+    if ((size_t)pl.workspace_bytes > (size_t)PK_STATIC_WS_BYTES) return PK_ERR_ARG;
+    void* ws = nullptr;
+    st = scratch_of_device(&ws);
+    if (st != PK_OK) return st;
+    return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
+                        activation, false, ws, (size_t)PK_STATIC_WS_BYTES, true, status, timeout_us, stream);
 }
 
 pk_status pk_ag_gemm_k_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -748,7 +797,7 @@ pk_status pk_ag_gemm_k(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtyp
                        const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
                        uint32_t* status, uint64_t timeout_us, void* stream) {
     return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
-                        activation, true, nullptr, 0, status, timeout_us, stream);
+                        activation, true, nullptr, 0, false, status, timeout_us, stream);
 }
 
 pk_status pk_emu_deliver_kchunks_dma(int P, int64_t M, int64_t K, int elem_bytes, const void* staging, void* A_gathered,

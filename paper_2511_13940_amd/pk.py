@@ -27,7 +27,7 @@ EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_a
            "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy",
            "pk_gemm_ar_plan", "pk_gemm_ar", "pk_emu_deliver_chunks_dma",
            "pk_gemm_rs_cols_plan", "pk_gemm_rs_cols", "pk_ag_gemm_k_plan", "pk_ag_gemm_k",
-           "pk_emu_deliver_kchunks_dma"]
+           "pk_emu_deliver_kchunks_dma", "pk_ag_gemm_static"]
 
 
 class Plan(ctypes.Structure):
@@ -81,6 +81,8 @@ def lib():
                                  i32, vp, u64, vp]
         L.pk_ag_gemm_k.restype = i32
         L.pk_ag_gemm_k.argtypes = ag_args
+        L.pk_ag_gemm_static.restype = i32
+        L.pk_ag_gemm_static.argtypes = ag_args
         L.pk_emu_deliver_kchunks_dma.restype = i32
         L.pk_emu_deliver_kchunks_dma.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, vp]
         L.pk_emu_deliver_chunks_dma.restype = i32
@@ -191,6 +193,14 @@ def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, c
                             _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus,
                             ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(workspace), _nbytes(workspace),
                             _ptr(status), timeout_us, _stream(stream)), "pk_ag_gemm")
+
+
+def pk_ag_gemm_static(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
+                      C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none"):
+    _check(lib().pk_ag_gemm_static(P, rank, M, N, K, _dt(dtype), _ptr(A_gathered), _ptr(B_local), _ptr(scale_a),
+                                   _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus,
+                                   ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(status),
+                                   timeout_us, _stream(stream)), "pk_ag_gemm_static")
 
 
 def pk_ag_gemm_k_plan(P, M, N, K, dtype):
