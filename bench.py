@@ -102,6 +102,8 @@ def main():
     # over ~50-70 ms (measured: the same launch takes 0.47 ms 4 ms after the start and 0.36 ms from 70 ms on).  A
     # deployment runs these kernels back to back, so the step is timed in that settled state: the preheat below is
     # the same step, untimed, for --preheat-ms of GPU time.  The first timed-order steps from idle are reported too.
+    epoch += 1
+    step(epoch)                                        # loads the code objects; not part of any timing
     torch.cuda.synchronize()
     time.sleep(0.2)
     cold = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
@@ -199,6 +201,8 @@ def main():
             "mfma_issue_share_inside_main_loops": round(32.0 * (c3.K // c3.P) * st_words[7] / max(st_words[6], 1), 4)},
     }
 
+    result.update(more_measurements(pk, wl, torch, np, locals()))
+    result["diagnosis"] = diagnosis(pk, torch, locals())
     if args.extras:
         result["extras"] = extras(pk, wl, torch, np, locals())
 
@@ -235,8 +239,17 @@ def main():
                 continue
             sel = rows3 // mp3 == q
             scat_err = max(scat_err, gate(og[q][rows3[sel] - q * mp3], own_rows[sel]))
+        # beside the gate: the largest error against the rms of the reference, and the share of outputs within one bf16
+        # unit in the last place of the correctly rounded reference (inputs ~N(0,1)/sqrt(K) make |ref| << 1, so the gate
+        # alone is an absolute 1e-2)
+        def ulp_stats(g, r):
+            rb = codec.bf16_decode(codec.bf16_encode(r))
+            ulp = np.maximum(np.abs(rb), 2.0 ** -126) * 2.0 ** -7
+            return {"max_abs_err_over_rms_ref": float(np.max(np.abs(g - r)) / np.sqrt(np.mean(r * r))),
+                    "share_within_1_bf16_ulp_of_rounded_ref": float(np.mean(np.abs(g - rb) <= ulp))}
         result["parity"] = {"metric": "max|gpu-ref|/(|ref|+1) on the sampled rows", "gemm_rs_out": gate(got3, ref3),
-                            "gemm_rs_outgoing": scat_err, "ag_gemm_C": gate(got4, c_rows), "tolerance": 1e-2}
+                            "gemm_rs_outgoing": scat_err, "ag_gemm_C": gate(got4, c_rows), "tolerance": 1e-2,
+                            "gemm_rs_out_detail": ulp_stats(got3, ref3), "ag_gemm_C_detail": ulp_stats(got4, c_rows)}
         assert max(result["parity"]["gemm_rs_out"], scat_err, result["parity"]["ag_gemm_C"]) <= 1e-2, result["parity"]
 
     result["setup_seconds"] = round(gen_s, 1)
@@ -256,6 +269,206 @@ def measured_traffic():
                     out[label] = int(fetch) + int(write)
     except OSError:
         pass
+    return out
+
+
+def _timeit(torch, stream, fn, n=20, w=5, st=None):
+    st = st or stream
+    for _ in range(w):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(st)
+    for _ in range(n):
+        fn()
+    b.record(st)
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / n
+
+
+def more_measurements(pk, wl, torch, np, L):
+    """The other figures of the measurement plan, all in the settled clock state: the Table-3-style pair for cfg3 (bare
+    GEMM against the fused op), cfg5 (fp8, HBM-bound) with its own roofline, the live-arrival cases on a compute-unit
+    partition, and the gather phase alone."""
+    c3, c4, rank, stream, status = L["c3"], L["c4"], L["rank"], L["stream"], L["status"]
+    out = {}
+    timeit = lambda fn, n=20, w=5, st=None: _timeit(torch, stream, fn, n, w, st)
+    ep = [20 * 10 ** 6]
+
+    # --- cfg3: GEMM alone (same kernel, bf16 output, no flags) against GEMM + reduce-scatter, as the paper's Table 3 ---
+    m, n, k = c3.local_mnk
+    Cg = torch.zeros((m, n), dtype=torch.int16, device="cuda")
+    t_gemm = timeit(lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", L["A3"], L["B3"], None, None, None, 1, Cg, status))
+
+    def fused():
+        ep[0] += 1
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                      L["flags_in"], L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, status)
+    t_fused = timeit(fused)
+    out["table3_style_cfg3"] = {"t_gemm_ms": round(t_gemm, 4), "t_fused_ms": round(t_fused, 4),
+                                "comm_ratio": round((t_fused - t_gemm) / t_fused, 4),
+                                "gemm_TFLOP/s": round(c3.flops / (t_gemm * 1e-3) / 1e12, 1),
+                                "fused_TFLOP/s": round(c3.flops / (t_fused * 1e-3) / 1e12, 1)}
+    del Cg
+
+    # --- gather phase alone: the emulated communicator moving the 7 peer chunks of cfg4 with 256 workgroups ---
+    staging = L["A4"].clone()
+    counters = torch.zeros(pk.EMU_MAX_ORDER, dtype=torch.int32, device="cuda")
+    order = L["i4"]["order"]
+    moved = 2 * (c4.P - 1) * (c4.M // c4.P) * c4.K * 2
+
+    def gather():
+        counters.zero_()
+        pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], L["chunk_flags"], 0x7FFFFFFF, order, 0, counters, n_wg=256)
+    t_g = timeit(gather)
+    out["gather_phase_cfg4"] = {"ms": round(t_g, 4), "GB/s": round(moved / (t_g * 1e-3) / 1e9, 1),
+                                "frac_of_hbm_peak": round(moved / (t_g * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "workgroups": 256}
+
+    # --- live arrival on a compute-unit partition (communicator on COMM compute units, the op on the others) ---
+    COMM = 32
+    h_comp, h_comm = pk.pk_partition_create(COMM)
+    comp, side = torch.cuda.ExternalStream(h_comp), torch.cuda.ExternalStream(h_comm)
+    flags_live = torch.zeros(c4.P, dtype=torch.int32, device="cuda")
+    done = torch.cuda.Event()
+    torch.cuda.synchronize()
+
+    def ag_live():
+        ep[0] += 1
+        done.record(comp)
+        side.wait_event(done)
+        with torch.cuda.stream(side):
+            counters.zero_()
+        pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_live, ep[0], order, 0, counters,
+                                 stream=side, n_wg=8 * COMM)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_live, ep[0], L["C4"],
+                      status, comm_cus=COMM, stream=comp)
+        comp.wait_stream(side)
+    t_ag_live = timeit(ag_live, st=comp)
+    t_ag_pre = timeit(lambda: pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None,
+                                            L["chunk_flags"], 1, L["C4"], status, comm_cus=COMM, stream=comp), st=comp)
+    flags_live3 = torch.zeros_like(L["flags_in"])
+    stage3 = L["part"].clone()
+    p3 = L["p3"]
+    peers = [q for q in range(c3.P) if q != rank]
+
+    def rs_live():
+        ep[0] += 1
+        done.record(comp)
+        side.wait_event(done)
+        pk.pk_emu_deliver_partials(c3.P, c3.M, c3.N, p3.tile_m, p3.tile_n, stage3, L["part"], flags_live3, ep[0],
+                                   peers, 0, stream=side, n_wg=8 * COMM)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                      flags_live3, L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, status, comm_cus=COMM, stream=comp)
+        comp.wait_stream(side)
+    t_rs_live = timeit(rs_live, st=comp)
+
+    def rs_pre():
+        ep[0] += 1
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                      L["flags_in"], L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, status, comm_cus=COMM, stream=comp)
+    t_rs_pre = timeit(rs_pre, st=comp)
+    torch.cuda.synchronize()
+    pk.pk_partition_destroy(h_comp, h_comm)
+    out["live_arrival"] = {
+        "comm_cus": COMM,
+        "ag_gemm_cfg4": {"t_fused_live_ms": round(t_ag_live, 4), "t_fused_prelanded_same_partition_ms": round(t_ag_pre, 4),
+                         "live_over_prelanded": round(t_ag_live / t_ag_pre, 3)},
+        "gemm_rs_cfg3": {"t_fused_live_ms": round(t_rs_live, 4), "t_fused_prelanded_same_partition_ms": round(t_rs_pre, 4),
+                         "live_over_prelanded": round(t_rs_live / t_rs_pre, 3)}}
+    del staging, stage3
+
+    # --- cfg5: fp8 e4m3 GEMM + reduce-scatter; HBM-bound (2.28 GB of mandatory traffic for 1.1e12 flop) ---
+    c5 = wl.CONFIGS["cfg5"]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(251113945)
+    p5 = pk.pk_gemm_rs_plan(c5.P, c5.M, c5.N, c5.K, c5.dtype)
+    mp5, k5 = c5.M // c5.P, c5.K // c5.P
+    # operands: N(0,1)/sqrt(K) quantised to e4m3 with a per-tensor scale amax/448 (drawn on the device: parity of this
+    # configuration is the tests' business); peer partials N(0, sigma_p^2) as in the recipe
+    def q8(rows, cols):
+        x = torch.randn((rows, cols), generator=gen, device="cuda") / c5.K ** 0.5
+        sc = x.abs().max() / 448.0
+        return (x / sc).to(torch.float8_e4m3fn).view(torch.uint8), sc.reshape(1).float()
+    A5, sa5 = q8(c5.M, k5)
+    B5, sb5 = q8(k5, c5.N)
+    part5 = torch.randn((c5.P, mp5, c5.N), generator=gen, device="cuda") * (k5 ** 0.5 / c5.K)
+    outg5 = torch.zeros((c5.P, mp5, c5.N), dtype=torch.float32, device="cuda")
+    out5 = torch.zeros((mp5, c5.N), dtype=torch.int16, device="cuda")
+    fin5 = torch.full((c5.P, p5.flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    fin5[rank].zero_()
+    fout5 = torch.zeros_like(fin5)
+
+    def rs5(phases):
+        def f():
+            if phases & 1:
+                ep[0] += 1
+            pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part5, outg5, fin5, fout5, ep[0], out5,
+                          phases, status)
+        return f
+    t5 = timeit(rs5(pk.PHASE_ALL), n=10, w=4)
+    t5g = timeit(rs5(pk.PHASE_GEMM), n=10, w=4)
+    t5r = timeit(rs5(pk.PHASE_REDUCE), n=10, w=4)
+    bytes5 = 2 * c5.M * k5 + 2 * c5.M * c5.N * 4 + mp5 * c5.N * 2
+    red5 = c5.M * c5.N * 4 + mp5 * c5.N * 2
+    out["cfg5_fp8_gemm_rs"] = {
+        "ms": round(t5, 4), "TFLOP/s": round(c5.flops / (t5 * 1e-3) / 1e12, 1),
+        "roofline": {"bound": "hbm", "achieved": round(bytes5 / (t5 * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(bytes5 / (t5 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "algorithmic_bytes": bytes5, "traffic": None},
+        "gemm_phase_ms": round(t5g, 4), "gemm_phase_TFLOP/s": round(c5.flops / (t5g * 1e-3) / 1e12, 1),
+        "gemm_phase_frac_of_fp8_mfma_peak": round(c5.flops / (t5g * 1e-3) / 1e12 / PEAK_TFLOPS["fp8"], 4),
+        "reduce_phase_ms": round(t5r, 4), "reduce_phase_GB/s": round(red5 / (t5r * 1e-3) / 1e9, 1)}
+    assert status[0].item() == 0, f"device status {status.tolist()}"
+    return out
+
+
+def diagnosis(pk, torch, L):
+    """What holds the bf16 GEMM below the MFMA peak, measured through the product entry point (a bare GEMM of the cfg3
+    local shape, 4 tiles of 256 x 256 x 3584 per workgroup) with the kernel's own clock report: the core clock the chip
+    holds as a function of (a) how many compute units are busy, (b) the bit activity of the operands, (c) the time since
+    the load began.  The instruction schedule is the same in every row."""
+    stream, status = L["stream"], L["status"]
+    n, k = 8192, 3584
+    A, B = L["A3"], L["B3"]                      # 8192 x 3584 and 3584 x 8192, N(0,1)/sqrt(K) in bf16
+    C = torch.zeros((8192, n), dtype=torch.int16, device="cuda")
+
+    def run(m, comm, a, b, reps=150):
+        fn = lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", a, b, None, None, None, 1, C, status, comm_cus=comm)
+        ms = _timeit(torch, stream, fn, n=reps, w=reps)
+        st = [x & 0xFFFFFFFF for x in status.tolist()]
+        return {"ms": round(ms, 4), "TFLOP/s": round(2.0 * m * n * k / (ms * 1e-3) / 1e12, 1),
+                "core_clock_MHz": round(100.0 * st[5] / max(st[4], 1)),
+                "mfma_issue_share_in_main_loops": round(32.0 * k * st[7] / max(st[6], 1), 3),
+                "main_loop_share_of_cycles": round(st[6] / max(st[5], 1), 3)}
+    out = {"kernel": "gemm_kernel<256,256,bf16> as a bare GEMM, n = 8192, k = 3584, m = 32 rows per workgroup x 4 tiles",
+           "active_compute_units": {}, "operand_bit_activity": {}}
+    for comm in (0, 32, 64, 128, 192):
+        out["active_compute_units"][str(256 - comm)] = run((256 - comm) * 32, comm, A, B)
+    out["operand_bit_activity"]["N(0,1)/sqrt(K)"] = out["active_compute_units"]["256"]
+    ones_a = torch.full((8192, k), 0x3F80, dtype=torch.int16, device="cuda")
+    ones_b = torch.full((k, n), 0x3F80, dtype=torch.int16, device="cuda")
+    out["operand_bit_activity"]["all 1.0"] = run(8192, 0, ones_a, ones_b)
+    ones_a.zero_()
+    ones_b.zero_()
+    out["operand_bit_activity"]["all 0.0"] = run(8192, 0, ones_a, ones_b)
+    del ones_a, ones_b
+    # the governor's answer to a load that starts from idle: time per launch against the time since the first launch
+    import time as _t
+    torch.cuda.synchronize()
+    _t.sleep(0.5)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(41)]
+    evs[0].record(stream)
+    for i in range(40):
+        for _ in range(5):
+            pk.pk_ag_gemm(1, 0, 8192, n, k, "bf16", A, B, None, None, None, 1, C, status)
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    t, ramp = 0.0, []
+    for i in range(40):
+        dt = evs[i].elapsed_time(evs[i + 1])
+        t += dt
+        if i in (0, 1, 2, 4, 7, 11, 15, 19, 24, 29, 34, 39):
+            ramp.append([round(t, 1), round(dt / 5, 4)])
+    out["ms_per_launch_against_ms_since_start_from_idle"] = ramp
     return out
 
 
