@@ -413,6 +413,27 @@ def test_abs_product_bounds_the_sum():
     assert np.all(mag > 0)
 
 
+def test_abs_product_equals_an_integer_sum_of_magnitudes():
+    """Pin of the bound helper: on small-integer operands sum_k |a_ik| |b_kj| is exact in Python integers (a factor,
+    a dropped absolute value or a transposed operand would show), and an fp8 scale pair enters once, in magnitude."""
+    rng = np.random.default_rng(11)
+    for (m, k, n) in ((3, 5, 4), (7, 13, 2), (1, 1, 1)):
+        ia = rng.integers(-3, 4, size=(m, k))
+        ib = rng.integers(-3, 4, size=(k, n))
+        a_bits = codec.bf16_encode(ia.astype(np.float64))
+        b_bits = codec.bf16_encode(ib.astype(np.float64))
+        want = [[sum(abs(int(ia[i, t])) * abs(int(ib[t, j])) for t in range(k)) for j in range(n)] for i in range(m)]
+        got = tp_gemm.abs_product(a_bits, b_bits, "bf16")
+        assert got.shape == (m, n)
+        assert np.array_equal(got, np.array(want, dtype=np.float64))
+        assert np.array_equal(tp_gemm.abs_product(a_bits, b_bits, "bf16", rows=[m - 1]), np.array(want, dtype=np.float64)[m - 1:])
+    # e4m3: codes 0x38 = 1, 0x40 = 2, 0xC0 = -2; scales 0.5 and -3 -> |scale| = 1.5
+    a8 = np.array([[0x38, 0xC0], [0x40, 0x40]], dtype=np.uint8)
+    b8 = np.array([[0xC0], [0x38]], dtype=np.uint8)
+    got = tp_gemm.abs_product(a8, b8, "fp8", 0.5, -3.0)
+    assert np.array_equal(got, 1.5 * np.array([[1 * 2 + 2 * 1], [2 * 2 + 2 * 1]], dtype=np.float64))
+
+
 def test_shape_errors():
     a = np.zeros((4, 6), np.uint16)
     with pytest.raises(ValueError):
