@@ -15,8 +15,8 @@
  *
  * Peer ranks are not real GPUs here.  What a peer would write into this rank's memory over the fabric (its
  * partial sums for this rank's output shard; its row-chunk of A) lives in buffers in this GPU's HBM and is
- * announced through ready flags, exactly as a one-way push into pre-allocated destination buffers would be
- * (paper section 3.1.4, "pre-allocated destination buffers, direct one-way transfers").  The pk_emu_* calls
+ * announced through ready flags, exactly as a peer pushing one way into buffers that the receiver allocated up
+ * front would leave it (paper section 3.1.4).  The pk_emu_* calls
  * play the peers for tests and benchmarks; they are not part of the method.
  *
  * Flags (the paper's barrier objects and signal/wait primitives, section 3.2.2 and appendix C): a flag is a
@@ -65,6 +65,13 @@ typedef enum {
 
 typedef enum { PK_BF16 = 0, PK_FP8_E4M3 = 1 } pk_dtype;
 
+/* memory layout of the second operand of pk_gemm_rs / pk_ag_gemm.  The paper gives its dimensions (K x N, section 4,
+ * experimental setup) and not its memory order; the default is the matrix as written, row-major.  A weight matrix
+ * that a caller keeps transposed (N x K row-major: every column of B contiguous along k, the usual storage of a linear
+ * layer's weight) can be passed as it is with PK_B_K_CONTIGUOUS: the product is the same, both operands then reach
+ * the matrix cores through 16-byte LDS reads and the transposing reads of the row-major path are not needed. */
+typedef enum { PK_B_ROW_MAJOR = 0, PK_B_K_CONTIGUOUS = 1 } pk_b_layout;
+
 #define PK_STATUS_WORDS 8    /* size of every `status` buffer, in uint32 */
 
 /* element type of the partial slots of pk_gemm_rs / pk_gemm_ar (`partials`, `outgoing`) */
@@ -75,7 +82,7 @@ typedef enum {
                               rounded to bf16 once before the fp32 sum */
 } pk_partial_dtype;
 
-/* non-linearity fused into pk_ag_gemm's epilogue (paper section 4.1: AG + GEMM, "a non-linear activation", GEMM + RS);
+/* non-linearity between the two GEMMs of the MLP (paper section 4.1, which does not name one), fused into pk_ag_gemm's epilogue;
  * evaluated in fp32 on the accumulator, before the rounding to bf16 */
 typedef enum {
     PK_ACT_NONE = 0,
@@ -129,7 +136,8 @@ const char* pk_status_str(int status);
  * array and the owner adds the P slots once, so the result does not depend on arrival order.
  *
  *   A_local   M x K/P      bf16 (2 B) or e4m3 (1 B)
- *   B_local   K/P x N      same element type
+ *   B_local   K/P x N      same element type; with b_layout = PK_B_K_CONTIGUOUS: N x K/P, the same matrix transposed
+ *                          (fp32 slots only; PK_ERR_ARG otherwise)
  *   scale_a, scale_b       one fp32 each, fp8 only (NULL for bf16)
  *   partials  [P][M/P][N]  fp32, or bf16 with partial_dt = PK_PARTIAL_BF16.  Slot q != rank is written by peer q
  *                          (or by pk_emu_deliver_partials); slot `rank` is written by this call.
@@ -152,7 +160,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      void* partials, void* outgoing,
                      uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
                      void* out_shard, uint32_t phases, int comm_cus, int partial_dt /* pk_partial_dtype */,
-                     void* workspace, size_t workspace_bytes,
+                     int b_layout /* pk_b_layout */, void* workspace, size_t workspace_bytes,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
@@ -222,7 +230,7 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  *
  *   A_gathered  M x K   rows R_q = chunk q.  Chunk `rank` is valid at the call; chunk q != rank is valid
  *                       once chunk_flags[q] has reached `epoch`.
- *   B_local     K x N/P
+ *   B_local     K x N/P; with b_layout = PK_B_K_CONTIGUOUS: N/P x K, the same matrix transposed
  *   chunk_flags [P]
  *   C_local     M x N/P bf16
  *
@@ -240,7 +248,7 @@ pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch,
                      void* C_local, int comm_cus, int activation /* pk_activation */,
-                     void* workspace, size_t workspace_bytes,
+                     int b_layout /* pk_b_layout */, void* workspace, size_t workspace_bytes,
                      uint32_t* status, uint64_t timeout_us, void* stream);
 
 /*
@@ -299,7 +307,7 @@ pk_status pk_emu_deliver_chunks(int P, int64_t M, int64_t K, int elem_bytes,
                                 uint32_t* chunk_flags, uint32_t epoch,
                                 const int* order /* host */, int n_order, uint32_t gap_us, int n_wg,
                                 uint32_t* counters, void* stream);
-/* The same delivery of chunks without communicator workgroups (paper section 3.1.1, host-initiated copy engine
+/* The same delivery of chunks without communicator workgroups (paper section 3.1.2, host-initiated copy engine
  * transfers): one device-to-device copy per chunk on `stream`, each followed by a stream memory operation that writes the
  * chunk's flag.  No compute unit is taken from the consumer; granularity is a whole chunk. */
 pk_status pk_emu_deliver_chunks_dma(int P, int64_t M, int64_t K, int elem_bytes,

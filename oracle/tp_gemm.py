@@ -211,8 +211,8 @@ ACTIVATIONS = ("none", "relu", "gelu_tanh", "silu")
 
 
 def activation(x, kind):
-    """The non-linearity between the two GEMMs of the tensor-parallel MLP (section 4.1 names "a non-linear
-    activation" without fixing one; these are the usual choices), elementwise in float64:
+    """The non-linearity between the two GEMMs of the tensor-parallel MLP (section 4.1 asks for one without
+    fixing which; these are the usual choices), elementwise in float64:
       relu(x) = max(x, 0);  silu(x) = x / (1 + exp(-x));
       gelu_tanh(x) = x/2 * (1 + tanh( sqrt(2/pi) * (x + 0.044715 x^3) )).
     """

@@ -93,7 +93,9 @@ constexpr int gemm_lds_bytes() { return NS * (BM + BN) * KB + kEpiStageBytes; }
 // s_waitcnt immediate for vmcnt(N) lgkmcnt(0) (gfx9 encoding, expcnt left alone)
 constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4); }
 
-template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
+// BT: the second operand is stored k-contiguous (N x K row-major, the transpose of the K x N matrix): its tile then has
+// the layout of the A tile and its fragments come in with the same 16-byte reads, no transposing reads.
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
 __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     PK_LDS char* lds = (PK_LDS char*)smem_generic;
@@ -134,7 +136,11 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     const uint32_t a_row_off = (uint32_t)(wm * (BM / WM) + (l & 31)) * KB;
     const int s16 = l & 15, nhalf = (l >> 4) & 1;
     uint32_t b_off[TN];
-    if constexpr (!FP8) {
+    const uint32_t bt_row_off = (uint32_t)(A_BYTES + (wn * (BN / WN) + (l & 31)) * KB);   // BT: B tile = BN rows of KB bytes
+    if constexpr (BT) {
+#pragma unroll
+        for (int tj = 0; tj < TN; ++tj) b_off[tj] = bt_row_off + (uint32_t)(tj * 32 * KB);
+    } else if constexpr (!FP8) {
         // bf16 B tile: panels of 64 columns (128 bytes per k-row, k-rows consecutive);
         // inside a row the two 32-byte pieces of each 64-byte half trade places on k-rows with bit 1 set
         static_assert((BN / WN) % 64 == 0, "a wave column covers whole 64-column panels");
@@ -159,7 +165,21 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     // MFMAs need them: B fragments first, then A fragments.
     constexpr int NU = TN + TM;
     auto read_unit = [&](PK_LDS char* st, int kk, int u, frag_t (&af)[TM], frag_t (&bfr)[TN]) {
-        if constexpr (!FP8) {
+        if constexpr (BT) {
+            // both operands: rows of KB bytes, 16-byte chunks XOR-swizzled by row; rows of a fragment differ by multiples of 32
+            const uint32_t base = u < TN ? b_off[u] : a_row_off + (uint32_t)((u - TN) * 32 * KB);
+            if constexpr (!FP8) {
+                const bf16x8 v = *(PK_LDS bf16x8*)(st + base + (uint32_t)((((2 * kk + h) ^ fa) & (CPA - 1)) * 16));
+                if (u < TN) bfr[u] = v;
+                else af[u - TN] = v;
+            } else {
+                i32x4 x0 = *(PK_LDS i32x4*)(st + base + (uint32_t)((((4 * kk + 2 * h) ^ fa) & (CPA - 1)) * 16));
+                i32x4 x1 = *(PK_LDS i32x4*)(st + base + (uint32_t)((((4 * kk + 2 * h + 1) ^ fa) & (CPA - 1)) * 16));
+                const i32x8 v = __builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7);
+                if (u < TN) bfr[u] = v;
+                else af[u - TN] = v;
+            }
+        } else if constexpr (!FP8) {
             if (u < TN) {
                 const int tj = u;
                 s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -376,7 +396,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
         uint32_t a_voff[NA], b_voff[NB];           // per-lane byte offsets from the k-tile base pointers
         const char* a_base = g.A;                    // wave-uniform, advanced by one k-tile per issue
         const char* b_base = g.B;
-        const int64_t b_step = (int64_t)B_ROWS * g.ldb;
+        const int64_t b_step = BT ? (int64_t)KB : (int64_t)B_ROWS * g.ldb;   // bytes from one k-tile of B to the next
         // k-tiles handled between two pipeline fills: all of them, or one column chunk of A at a time (EPI_AGK, own
         // chunk); once this workgroup has seen every chunk, its later tiles run the whole k range in one go
         const bool by_chunk = (EPI == EPI_AGK) && seen_chunks != all_chunks;
@@ -400,7 +420,16 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                     a_voff[j] = (uint32_t)((int64_t)grow * g.lda + (cp ^ fA(r)) * 16);
                 }
             }
-            if constexpr (!FP8) {
+            if constexpr (BT) {
+                // as the A tile: 1 KB block = 64 / CPA rows (columns of the product) of KB bytes
+                const int r_in = l / CPA, cp = l % CPA;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int r = (64 / CPA) * (j * NW + w) + r_in;
+                    const int gcol = min(col0 + r, g.n - 1);        // edge tile: valid memory, never stored
+                    b_voff[j] = (uint32_t)((int64_t)gcol * g.ldb + (cp ^ fA(r)) * 16);
+                }
+            } else if constexpr (!FP8) {
                 // 1 KB block bi of the B tile = 8 k-rows of one 64-column panel
                 const int kr_in = l >> 3, cp = l & 7;
                 const int n_bytes = g.n * 2;

@@ -338,11 +338,11 @@ static pk_status make_plan_cols(int P, int64_t M, int64_t N, int64_t K, pk_dtype
 
 // Persistent launch: one workgroup per CU (a multiple of 8 so that workgroup id mod 8 stays the XCD), or fewer
 // when there are fewer tile slots.
-template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI>
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
 static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream) {
     // the dynamic LDS size of this instantiation is raised once per device (bit d of `configured` = done on device d)
     static std::atomic<uint64_t> configured{0};
-    auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI>;
+    auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT>;
     constexpr int lds = gemm_lds_bytes<BM, BN, KB, NS>();
     a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
     int dev = 0;
@@ -377,7 +377,21 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size
 
 template <int EPI>
 static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const TileCfg& tc, bool fp8,
-                               void* ws, size_t ws_bytes, hipStream_t stream) {
+                               void* ws, size_t ws_bytes, hipStream_t stream, bool bt = false) {
+    if (bt) {
+        // second operand stored k-contiguous: built for the two base epilogues only
+        if constexpr (EPI == EPI_RS || EPI == EPI_AG) {
+            // 128-byte k-tiles in a ring of 2 stages: a k-contiguous operand is fetched as one piece per row and k-tile, and
+            // 64-byte pieces use half of every 128-byte line they touch (measured: 7% slower than the row-major path)
+            if (tc.bm == 256)
+                return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream)
+                           : launch_gemm<256, 256, 2, 4, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream);
+            return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream)
+                       : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream);
+        } else {
+            return PK_ERR_ARG;
+        }
+    }
     if (tc.bm == 256) {
         // 8 waves, 64-byte k-tiles (32 bf16 or 64 fp8 of k) in a ring of 4 LDS stages
         return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
@@ -479,14 +493,17 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
                               void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out,
                               uint32_t epoch, void* out_shard, const AllReduceOut* ar, uint32_t phases, int comm_cus,
                               int partial_dt, bool cols, void* ws, size_t ws_bytes, uint32_t* status, uint64_t timeout_us,
-                              void* stream) {
+                              void* stream, int b_layout = PK_B_ROW_MAJOR) {
     pk_plan pl;
     pk_status st = cols ? make_plan_cols(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, true, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
     if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
     if (partial_dt != PK_PARTIAL_F32 && partial_dt != PK_PARTIAL_BF16) return PK_ERR_DTYPE;
+    if (b_layout != PK_B_ROW_MAJOR && b_layout != PK_B_K_CONTIGUOUS) return PK_ERR_ARG;
     const bool bf16_slots = partial_dt == PK_PARTIAL_BF16;
+    const bool bt = b_layout == PK_B_K_CONTIGUOUS;
+    if (bt && bf16_slots) return PK_ERR_ARG;
     const bool fp8 = dt == PK_FP8_E4M3;
     const bool do_gemm = phases & PK_PHASE_GEMM, do_reduce = phases & PK_PHASE_REDUCE;
     if (!partials || !flags_in || !status) return PK_ERR_NULL;
@@ -509,7 +526,7 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.A = (const char*)A_local;
         a.B = (const char*)B_local;
         a.lda = pl.local_k * elem;
-        a.ldb = pl.local_n * elem;
+        a.ldb = (bt ? pl.local_k : pl.local_n) * elem;
         a.n = (int32_t)pl.local_n;
         a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
         a.rows_per_shard = (int32_t)rows;
@@ -536,7 +553,7 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
         st = bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s)
-                        : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s);
+                        : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, bt);
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
@@ -605,13 +622,16 @@ static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
                               const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
                               const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
                               bool k_chunks, void* ws, size_t ws_bytes, bool ws_is_static, uint32_t* status, uint64_t timeout_us,
-                              void* stream) {
+                              void* stream, int b_layout = PK_B_ROW_MAJOR) {
     pk_plan pl;
     pk_status st = k_chunks ? make_plan_ag_k(P, M, N, K, dt, &pl) : make_plan(P, M, N, K, dt, false, &pl);
     if (st != PK_OK) return st;
     if (rank < 0 || rank >= P) return PK_ERR_RANK;
     if (comm_cus < 0 || comm_cus > 4096) return PK_ERR_ARG;
     if (activation < PK_ACT_NONE || activation > PK_ACT_SILU) return PK_ERR_ARG;
+    if (b_layout != PK_B_ROW_MAJOR && b_layout != PK_B_K_CONTIGUOUS) return PK_ERR_ARG;
+    const bool bt = b_layout == PK_B_K_CONTIGUOUS;
+    if (bt && k_chunks) return PK_ERR_ARG;
     const bool fp8 = dt == PK_FP8_E4M3;
     if (!A_gathered || !B_local || !C_local || !status) return PK_ERR_NULL;
     if (P > 1 && !chunk_flags) return PK_ERR_NULL;
@@ -623,7 +643,7 @@ static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     a.A = (const char*)A_gathered;
     a.B = (const char*)B_local;
     a.lda = pl.local_k * elem;
-    a.ldb = pl.local_n * elem;
+    a.ldb = (bt ? pl.local_k : pl.local_n) * elem;
     a.n = (int32_t)pl.local_n;
     a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
     // row chunks: one scheduling group per chunk, visited from the own one; column chunks: every tile needs every chunk
@@ -654,7 +674,7 @@ static pk_status ag_gemm_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.ws_epoch = 1;
     }
     return k_chunks ? dispatch_gemm<EPI_AGK>(a, a.wg_per_group, comm_cus, tc, fp8, nullptr, 0, (hipStream_t)stream)
-                    : dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, ws, ws_bytes, (hipStream_t)stream);
+                    : dispatch_gemm<EPI_AG>(a, a.wg_per_group * P, comm_cus, tc, fp8, ws, ws_bytes, (hipStream_t)stream, bt);
 }
 
 static pk_status make_order(const int* order, int n_order, int P, EmuOrder* o) {
@@ -700,13 +720,13 @@ pk_status pk_ag_gemm_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, p
 pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_local, const void* B_local, const float* scale_a, const float* scale_b,
                      void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
-                     void* out_shard, uint32_t phases, int comm_cus, int partial_dt, void* workspace,
+                     void* out_shard, uint32_t phases, int comm_cus, int partial_dt, int b_layout, void* workspace,
                      size_t workspace_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
     if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
     if (!aligned16(workspace)) return PK_ERR_ALIGN;
     return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
                         flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, false, workspace, workspace_bytes,
-                        status, timeout_us, stream);
+                        status, timeout_us, stream, b_layout);
 }
 
 pk_status pk_gemm_rs_cols_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan) {
@@ -766,10 +786,11 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
 pk_status pk_ag_gemm(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
                      const void* A_gathered, const void* B_local, const float* scale_a, const float* scale_b,
                      const uint32_t* chunk_flags, uint32_t epoch, void* C_local, int comm_cus, int activation,
-                     void* workspace, size_t workspace_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
+                     int b_layout, void* workspace, size_t workspace_bytes, uint32_t* status, uint64_t timeout_us,
+                     void* stream) {
     if (!aligned16(workspace)) return PK_ERR_ALIGN;
     return ag_gemm_impl(P, rank, M, N, K, dt, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch, C_local, comm_cus,
-                        activation, false, workspace, workspace_bytes, false, status, timeout_us, stream);
+                        activation, false, workspace, workspace_bytes, false, status, timeout_us, stream, b_layout);
 }
 
 pk_status pk_ag_gemm_static(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,

@@ -22,6 +22,7 @@ PARTIAL_F32, PARTIAL_BF16 = 0, 1
 PARTIALS = {"f32": PARTIAL_F32, "bf16": PARTIAL_BF16}
 EMU_MAX_ORDER = 64
 DTYPES = {"bf16": BF16, "fp8": FP8_E4M3}
+B_LAYOUTS = {"kn": 0, "nk": 1, 0: 0, 1: 1}          # "kn": K x N row-major (default); "nk": N x K row-major (k-contiguous)
 
 EXPORTS = ["pk_version", "pk_status_str", "pk_gemm_rs_plan", "pk_gemm_rs", "pk_ag_gemm_plan", "pk_ag_gemm",
            "pk_emu_deliver_chunks", "pk_emu_deliver_partials", "pk_probe_mfma", "pk_partition_create", "pk_partition_destroy",
@@ -65,9 +66,9 @@ def lib():
         L.pk_gemm_rs.restype = i32
         rs_args = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp, u32, i32, i32, vp, u64, vp]
         ag_args = [i32, i32, i64, i64, i64, i32, vp, vp, vp, vp, vp, u32, vp, i32, i32, vp, u64, vp]
-        L.pk_gemm_rs.argtypes = rs_args[:19] + [vp, ctypes.c_size_t] + rs_args[19:]
+        L.pk_gemm_rs.argtypes = rs_args[:19] + [i32, vp, ctypes.c_size_t] + rs_args[19:]
         L.pk_ag_gemm.restype = i32
-        L.pk_ag_gemm.argtypes = ag_args[:15] + [vp, ctypes.c_size_t] + ag_args[15:]
+        L.pk_ag_gemm.argtypes = ag_args[:15] + [i32, vp, ctypes.c_size_t] + ag_args[15:]
         L.pk_emu_deliver_chunks.restype = i32
         L.pk_emu_deliver_chunks.argtypes = [i32, i64, i64, i32, vp, vp, vp, u32, ctypes.POINTER(i32), i32, u32, i32, vp, vp]
         L.pk_emu_deliver_partials.restype = i32
@@ -150,10 +151,11 @@ def pk_ag_gemm_plan(P, M, N, K, dtype):
 
 def pk_gemm_rs(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, partials, outgoing,
                flags_in, flags_out, epoch, out_shard, phases, status, timeout_us=0, stream=None, comm_cus=0,
-               partial_dtype="f32", workspace=None):
+               partial_dtype="f32", workspace=None, b_layout="kn"):
     _check(lib().pk_gemm_rs(P, rank, M, N, K, _dt(dtype), _ptr(A_local), _ptr(B_local), _ptr(scale_a), _ptr(scale_b),
                             _ptr(partials), _ptr(outgoing), _ptr(flags_in), _ptr(flags_out), epoch,
-                            _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), _ptr(workspace), _nbytes(workspace),
+                            _ptr(out_shard), phases, comm_cus, _pdt(partial_dtype), B_LAYOUTS[b_layout], _ptr(workspace),
+                            _nbytes(workspace),
                             _ptr(status), timeout_us, _stream(stream)), "pk_gemm_rs")
 
 
@@ -188,10 +190,11 @@ def pk_gemm_ar(P, rank, M, N, K, dtype, A_local, B_local, scale_a, scale_b, part
 
 
 def pk_ag_gemm(P, rank, M, N, K, dtype, A_gathered, B_local, scale_a, scale_b, chunk_flags, epoch,
-               C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none", workspace=None):
+               C_local, status, timeout_us=0, stream=None, comm_cus=0, act="none", workspace=None, b_layout="kn"):
     _check(lib().pk_ag_gemm(P, rank, M, N, K, _dt(dtype), _ptr(A_gathered), _ptr(B_local), _ptr(scale_a),
                             _ptr(scale_b), _ptr(chunk_flags), epoch, _ptr(C_local), comm_cus,
-                            ACTIVATIONS[act] if isinstance(act, str) else int(act), _ptr(workspace), _nbytes(workspace),
+                            ACTIVATIONS[act] if isinstance(act, str) else int(act), B_LAYOUTS[b_layout], _ptr(workspace),
+                            _nbytes(workspace),
                             _ptr(status), timeout_us, _stream(stream)), "pk_ag_gemm")
 
 

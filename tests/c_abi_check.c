@@ -15,7 +15,7 @@ int main(void) {
         return 5;
     if (pk_gemm_rs_plan(3, 256, 256, 512, PK_BF16, &plan) != PK_ERR_SHAPE) return 6;
     if (pk_gemm_rs(2, 5, 256, 256, 512, PK_BF16, (void*)0x1000, (void*)0x2000, NULL, NULL, (void*)0x3000, (void*)0x4000,
-                   (uint32_t*)0x5000, (uint32_t*)0x6000, 1u, (void*)0x7000, PK_PHASE_ALL, 0, PK_PARTIAL_F32, NULL, 0,
+                   (uint32_t*)0x5000, (uint32_t*)0x6000, 1u, (void*)0x7000, PK_PHASE_ALL, 0, PK_PARTIAL_F32, PK_B_ROW_MAJOR, NULL, 0,
                    (uint32_t*)0x8000, 0, NULL) != PK_ERR_RANK)
         return 7;
     if (strcmp(pk_status_str(PK_OK), pk_status_str(PK_ERR_SHAPE)) == 0) return 8;

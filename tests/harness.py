@@ -70,8 +70,8 @@ def deliver_slots(P, M, N, tile_m, tile_n, staging, part, flags, epoch, order, g
 def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, phases=pk.PHASE_ALL,
                 withhold=None, lazy=False, partition=None, comm_cus=0, n_wg=0, partial_dtype="f32", cols=False,
-                workspace=None):
-    """One pk_gemm_rs call.  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
+                workspace=None, b_layout="kn"):
+    """One pk_gemm_rs call.  b_layout = "nk": B_bits is the transposed matrix (N x K/P).  partials: numpy [P][M/P][N] fp32 (slot `rank` ignored).
 
     partition = (compute_stream, comm_stream) handles from pk_partition_create: the op then runs on the first and
     the emulated peers on the second.
@@ -120,7 +120,7 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
         side = torch.cuda.Stream() if partition is None else torch.cuda.ExternalStream(partition[1])
         deliver_slots(P, P * mp, ncols, plan.tile_m, plan.tile_n, staging, part, flags_in, epoch, list(order), gap_us, side,
                       n_wg, s16)
-    extra = {} if cols else {"workspace": make_workspace(plan, workspace)}
+    extra = {} if cols else {"workspace": make_workspace(plan, workspace), "b_layout": b_layout}
     op(P, rank, M, N, K, dtype, A, B, sa, sb, part, outgoing if P > 1 else None,
        flags_in, flags_out if P > 1 else None, epoch, out, phases, status, timeout_us, stream=main,
        comm_cus=comm_cus, partial_dtype=partial_dtype, **extra)
@@ -136,8 +136,8 @@ def run_gemm_rs(P, rank, M, N, K, dtype, A_bits, B_bits, partials, scale_a=None,
 
 def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=None,
                 epoch=1, deliver="pre", order=None, gap_us=0, timeout_us=0, withhold=None, fetch_A=True,
-                comm_cus=0, n_wg=0, partition=None, act="none", workspace=None):
-    """One pk_ag_gemm call.  chunks: list of P numpy bit arrays (M/P x K).
+                comm_cus=0, n_wg=0, partition=None, act="none", workspace=None, b_layout="kn"):
+    """One pk_ag_gemm call.  b_layout = "nk": B_bits is the transposed matrix (N/P x K).  chunks: list of P numpy bit arrays (M/P x K).
 
     deliver = "pre": every chunk is in A_gathered with its flag set before the call.
     deliver = "emu": only the own chunk is in place; the others are filled with a poison pattern and
@@ -181,7 +181,7 @@ def run_ag_gemm(P, rank, M, N, K, dtype, chunks, B_bits, scale_a=None, scale_b=N
                                      n_wg=n_wg)
     ws = make_workspace(pk.pk_ag_gemm_plan(P, M, N, K, dtype), workspace)
     pk.pk_ag_gemm(P, rank, M, N, K, dtype, A, B, sa, sb, flags if P > 1 else None, epoch, C, status,
-                  timeout_us, stream=main, comm_cus=comm_cus, act=act, workspace=ws)
+                  timeout_us, stream=main, comm_cus=comm_cus, act=act, workspace=ws, b_layout=b_layout)
     torch.cuda.synchronize()
     return {"C_bits": bits_of(C), "status": status.cpu().numpy(), "A_after": A.cpu().numpy() if fetch_A else None,
             "flags": flags.cpu().numpy()}

@@ -62,8 +62,8 @@ def test_plan_errors(args, code):
 
 
 def _rs(P=2, rank=0, M=256, N=256, K=512, dt=pk.BF16, A=0x1000, B=0x2000, sa=None, sb=None, part=0x3000,
-        outg=0x4000, fin=0x5000, fout=0x6000, out=0x7000, phases=3, status=0x8000, pdt=0, ws=None, ws_bytes=0):
-    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, 0, pdt, ws, ws_bytes,
+        outg=0x4000, fin=0x5000, fout=0x6000, out=0x7000, phases=3, status=0x8000, pdt=0, ws=None, ws_bytes=0, bl=0):
+    return pk.lib().pk_gemm_rs(P, rank, M, N, K, dt, A, B, sa, sb, part, outg, fin, fout, 1, out, phases, 0, pdt, bl, ws, ws_bytes,
                                status, 0, None)
 
 
@@ -84,7 +84,9 @@ def test_gemm_rs_argument_errors_launch_nothing():
     assert _rs(M=255) == pk.ERR_SHAPE
     assert _rs(dt=5) == pk.ERR_DTYPE
     assert pk.lib().pk_gemm_rs(2, 0, 256, 256, 512, pk.BF16, 0x1000, 0x2000, None, None, 0x3000, 0x4000, 0x5000, 0x6000, 1,
-                               0x7000, 3, -8, 0, None, 0, 0x8000, 0, None) == pk.ERR_ARG      # comm_cus
+                               0x7000, 3, -8, 0, 0, None, 0, 0x8000, 0, None) == pk.ERR_ARG      # comm_cus
+    assert _rs(bl=2) == pk.ERR_ARG
+    assert _rs(bl=1, pdt=1) == pk.ERR_ARG                    # k-contiguous B is built for fp32 slots only
     assert _rs(ws=0x9004, ws_bytes=1 << 30) == pk.ERR_ALIGN
     assert _rs(pdt=2) == pk.ERR_DTYPE
     assert _rs(pdt=-1) == pk.ERR_DTYPE
@@ -94,8 +96,8 @@ def test_ag_gemm_argument_errors_launch_nothing():
     f = pk.lib().pk_ag_gemm
 
     def ag(P=4, rank=0, M=2048, N=4096, K=2048, dt=pk.BF16, A=0x1000, B=0x2000, flags=0x3000, C=0x4000, status=0x5000,
-           comm=0, act=0, ws=None, ws_bytes=0):
-        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, comm, act, ws, ws_bytes, status, 0, None)
+           comm=0, act=0, ws=None, ws_bytes=0, bl=0):
+        return f(P, rank, M, N, K, dt, A, B, None, None, flags, 1, C, comm, act, bl, ws, ws_bytes, status, 0, None)
 
     assert ag(rank=4) == pk.ERR_RANK
     assert ag(N=4098) == pk.ERR_SHAPE        # N % P
@@ -109,6 +111,7 @@ def test_ag_gemm_argument_errors_launch_nothing():
     assert ag(act=4) == pk.ERR_ARG
     assert ag(act=-1) == pk.ERR_ARG
     assert ag(ws=0x9008, ws_bytes=1 << 30) == pk.ERR_ALIGN
+    assert ag(bl=-1) == pk.ERR_ARG
 
 
 def test_emulator_argument_errors_launch_nothing():
