@@ -34,6 +34,8 @@ def main():
                     help="untimed sustained run of the same step before the warm-up steps: the clock governor needs "
                          "~70 ms of load to settle (0 = measure the cold-start transient instead)")
     ap.add_argument("--extras", action="store_true", help="also time the phases alone and the live-arrival variants")
+    ap.add_argument("--only-step", action="store_true",
+                    help="time the step and nothing else (for profiler runs: no other launches of the same kernels)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs one rank's share on ONE GPU (peers are emulated in the same HBM); "
@@ -143,6 +145,8 @@ def main():
     report = torch.zeros(4, dtype=torch.int64, device="cuda")
     sustained = {}
     for label, rnd in (("constant_operands", 0), ("random_operands", 1)):
+        if args.only_step:
+            break
         pk.pk_probe_mfma(2000, rnd, report)
         torch.cuda.synchronize()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -170,8 +174,10 @@ def main():
                 "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS["bf16"], 4), "traffic": traffic.get(dom),
                 "traffic_unit": "bytes beyond L2 per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, see profiles/)",
                 "kernel_ms": round(kernels[dom]["ms"], 4),
+                "traffic_source": "profiles/bench_step_hbm_traffic.txt (measured offline with rocprofv3 --pmc on the commit "
+                                  "named in that file; not re-measured by this run)",
                 "mfma_loop_sustained": sustained,
-                "frac_of_sustained_random": round(ach / sustained["random_operands"]["TFLOP/s"], 4)}
+                "frac_of_sustained_random": round(ach / sustained["random_operands"]["TFLOP/s"], 4) if sustained else None}
     reduce_roofline = {"bound": "hbm", "kernel": "reduce_kernel<8> (cfg3)",
                        "achieved": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"], 1), "peak": PEAK_HBM_GBS,
                        "unit": "GB/s", "frac": round(kernels["reduce_kernel<8> (cfg3)"]["GB/s"] / PEAK_HBM_GBS, 4),
@@ -201,8 +207,9 @@ def main():
             "mfma_issue_share_inside_main_loops": round(32.0 * (c3.K // c3.P) * st_words[7] / max(st_words[6], 1), 4)},
     }
 
-    result.update(more_measurements(pk, wl, torch, np, locals()))
-    result["diagnosis"] = diagnosis(pk, torch, locals())
+    if not args.only_step:
+        result.update(more_measurements(pk, wl, torch, np, locals()))
+        result["diagnosis"] = diagnosis(pk, torch, locals())
     if args.extras:
         result["extras"] = extras(pk, wl, torch, np, locals())
 
@@ -310,6 +317,34 @@ def more_measurements(pk, wl, torch, np, L):
                                 "gemm_TFLOP/s": round(c3.flops / (t_gemm * 1e-3) / 1e12, 1),
                                 "fused_TFLOP/s": round(c3.flops / (t_fused * 1e-3) / 1e12, 1)}
     del Cg
+
+    # --- variants of the two GEMM kernels, each timed alone back to back on the same buffers ---
+    plan4 = pk.pk_ag_gemm_plan(c4.P, c4.M, c4.N, c4.K, c4.dtype)
+    ws = torch.zeros(plan4.workspace_bytes // 4, dtype=torch.int32, device="cuda")
+    B4t, B3t = L["B4"].t().contiguous(), L["B3"].t().contiguous()
+
+    def ag(**kw):
+        def f():
+            ep[0] += 1
+            pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], kw.get("B", L["B4"]),
+                          None, None, L["chunk_flags"], ep[0], L["C4"], status, workspace=kw.get("workspace"),
+                          b_layout=kw.get("b_layout", "kn"))
+        return f
+
+    def rsg(**kw):
+        def f():
+            ep[0] += 1
+            pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], kw.get("B", L["B3"]), None, None, L["part"],
+                          L["outgoing"], L["flags_in"], L["flags_out"], ep[0], L["out3"], pk.PHASE_GEMM, status,
+                          b_layout=kw.get("b_layout", "kn"))
+        return f
+    t_ag, t_ag_sk, t_ag_bt = timeit(ag(), n=60, w=40), timeit(ag(workspace=ws), n=60, w=40), timeit(ag(B=B4t, b_layout="nk"), n=60, w=40)
+    t_rs, t_rs_bt = timeit(rsg(), n=60, w=40), timeit(rsg(B=B3t, b_layout="nk"), n=60, w=40)
+    out["kernel_variants_alone_ms"] = {
+        "ag_gemm_cfg4": {"whole_tiles_224_workgroups": round(t_ag, 4), "stream_k_tail_256_workgroups": round(t_ag_sk, 4),
+                         "b_k_contiguous": round(t_ag_bt, 4)},
+        "gemm_rs_cfg3_gemm_phase": {"b_row_major": round(t_rs, 4), "b_k_contiguous": round(t_rs_bt, 4)}}
+    del ws, B4t, B3t
 
     # --- gather phase alone: the emulated communicator moving the 7 peer chunks of cfg4 with 256 workgroups ---
     staging = L["A4"].clone()

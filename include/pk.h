@@ -115,7 +115,8 @@ typedef struct {
  * (paper section 3.1.3: the schedule depends on the problem size) and workgroups hand partial accumulator tiles to
  * one another through this memory.  Layout: PK_WS_FLAG_BYTES of ready flags, then one fp32 tile per workgroup.  The
  * caller zeroes the flag bytes once; afterwards the workspace belongs to one call site: its epochs must grow from
- * call to call, and two calls that may run at the same time must not share it.  workspace = NULL: whole tiles only.
+ * call to call, and two calls that may run at the same time must not share it.  workspace = NULL: whole tiles only (also
+ * with PK_B_K_CONTIGUOUS and with bf16 slots, for which the tail is not built).
  * A workspace smaller than plan.workspace_bytes may be rejected with PK_ERR_ARG.
  */
 #define PK_WS_FLAG_BYTES 4096

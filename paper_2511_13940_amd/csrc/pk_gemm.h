@@ -95,7 +95,8 @@ constexpr int waitcnt_vm_lgkm0(int n) { return (n & 15) | ((n >> 4) << 14) | (7 
 
 // BT: the second operand is stored k-contiguous (N x K row-major, the transpose of the K x N matrix): its tile then has
 // the layout of the A tile and its fragments come in with the same 16-byte reads, no transposing reads.
-template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
+// SK: built with the stream-K tail (its code paths cost registers, so launches that share out no tile use SK = false).
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false, bool SK = false>
 __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     PK_LDS char* lds = (PK_LDS char*)smem_generic;
@@ -246,7 +247,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     };
 
     auto signal_prev = [&]() {   // paper appendix C `signal` for the tile whose stores have completed
-        if (p_kind == UNIT_PART) {
+        if (SK && p_kind == UNIT_PART) {
             if (tid == 0) flag_publish(g.ws_flags + blockIdx.x, g.ws_epoch);
         } else if constexpr (IS_RS) {
             if (tid == 0 && !p_dead) {
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     constexpr int SK_Q = (KS % 2) ? 2 : 1, SK_MINP = 2 * NS;
     const int KT = g.ktiles;
     const int sk_x = blockIdx.x & 7, sk_j = blockIdx.x >> 3, sk_W = gridDim.x >> 3;
-    const int sk_R = (slots_total - g.sk_dp_slots) >> 3;
+    const int sk_R = SK ? (slots_total - g.sk_dp_slots) >> 3 : 0;
     auto sk_bnd = [&](int j) -> int {
         int b = (int)((int64_t)sk_R * KT * j / sk_W);
         b -= b % SK_Q;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                 slot_index = __builtin_ctzll(deferred);
                 deferred &= deferred - 1;
                 slot = (int)blockIdx.x + slot_index * (int)gridDim.x;
-            } else if (sk_c < sk_e) {
+            } else if (SK && sk_c < sk_e) {
                 const int i = sk_c / KT;
                 tile_end = (i + 1) * KT;
                 const int e = min(sk_e, tile_end);
@@ -480,7 +481,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 
         // ---- epilogue of the previous tile (the storer), under the latency of the loads just issued ----
         bool skip_epilogue = false;
-        if (p_q >= 0 && p_kind == UNIT_PART) {
+        if (SK && p_q >= 0 && p_kind == UNIT_PART) {
             // hand the raw accumulators to the owner of the tile: register image, 16 bytes per lane, written through
             char* wsb = g.ws_tiles + (int64_t)blockIdx.x * (BM * BN * 4) + (w * (TM * TN * 4)) * 1024 + l * 16;
 #pragma unroll
@@ -494,7 +495,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
                     }
             skip_epilogue = true;
         }
-        if (p_q >= 0 && p_kind == UNIT_HEAD) {
+        if (SK && p_q >= 0 && p_kind == UNIT_HEAD) {
             // add the other pieces of this tile: those of the following workgroups of this XCD whose ranges start inside it
             for (int jp = p_part_lo; jp < sk_W; ++jp) {
                 const int s0 = sk_bnd(jp);
@@ -652,7 +653,16 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
                 mfma_one(i / TN, i % TN, ca, cb);
-                if constexpr (READS) {
+                if constexpr (READS && FP8) {
+                    // 8-bit fragments are 8 registers each: two full sets next to the accumulators do not fit.  The MFMAs run
+                    // row by row (ti-major), so the A fragment of row ti is dead after MFMA ti*TN + TN-1, and the next step's
+                    // A fragment of that row is read right behind it, into the same registers; only the B fragments are double.
+                    if (i == 0) {
+#pragma unroll
+                        for (int u = 0; u < TN; ++u) read_unit(rd_stage, rd_kk, u, na, nb);
+                    }
+                    if (i % TN == TN - 1) read_unit(rd_stage, rd_kk, TN + i / TN, na, nb);
+                } else if constexpr (READS) {
                     if (i < H) {
 #pragma unroll
                         for (int u = (NU * i) / H; u < (NU * (i + 1)) / H; ++u) read_unit(rd_stage, rd_kk, u, na, nb);
@@ -764,7 +774,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     }
 
     // the last tile's stores: every wave waits for its write-through stores, then the flag is published
-    if (p_q >= 0 && (IS_RS || p_kind == UNIT_PART)) {
+    if (p_q >= 0 && (IS_RS || (SK && p_kind == UNIT_PART))) {
         __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
         __syncthreads();
         signal_prev();

@@ -338,13 +338,12 @@ static pk_status make_plan_cols(int P, int64_t M, int64_t N, int64_t K, pk_dtype
 
 // Persistent launch: one workgroup per CU (a multiple of 8 so that workgroup id mod 8 stays the XCD), or fewer
 // when there are fewer tile slots.
-template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
-static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream) {
-    // the dynamic LDS size of this instantiation is raised once per device (bit d of `configured` = done on device d)
-    static std::atomic<uint64_t> configured{0};
-    auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT>;
+// one launch of one instantiation; the dynamic LDS size of an instantiation is raised once per device
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT, bool SK>
+static pk_status launch_kernel(const GemmArgs& a, int grid, hipStream_t stream) {
+    static std::atomic<uint64_t> configured{0};              // bit d = done on device d
+    auto kern = gemm_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, SK>;
     constexpr int lds = gemm_lds_bytes<BM, BN, KB, NS>();
-    a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return PK_ERR_HIP;
     const uint64_t bit = 1ull << (dev & 63);
@@ -353,11 +352,19 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size
             return PK_ERR_HIP;
         configured.fetch_or(bit, std::memory_order_release);
     }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, stream, a);
+    return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
+}
+
+template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
+static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream) {
+    a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
+    constexpr bool HAS_SK = !BT && (EPI == EPI_RS || EPI == EPI_AG);   // the stream-K tail is built for these
     int grid = (num_cus() - comm_cus) / 8 * 8;
     if (grid < 8) grid = 8;
     a.sk_dp_slots = slots;
     const int rem = slots % grid;
-    if (ws && EPI != EPI_AGK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
+    if (ws && HAS_SK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
         // With a workspace every compute unit works to the end: whole rounds of tiles, then the k range of the left-over
         // tiles shared out evenly (448 slots on 256 CUs: 256 whole tiles, then 192 tiles as 256 pieces of 3/4 tile).
         if (ws_bytes < kWsFlagBytes + (size_t)grid * BM * BN * 4) return PK_ERR_ARG;
@@ -371,8 +378,10 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size
         const int even = ((slots + rounds - 1) / rounds + 7) / 8 * 8;
         if (even < grid) grid = even;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * WM * WN), lds, stream, a);
-    return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
+    if constexpr (HAS_SK) {
+        if (a.sk_dp_slots != slots) return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, true>(a, grid, stream);
+    }
+    return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, false>(a, grid, stream);
 }
 
 template <int EPI>
