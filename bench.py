@@ -452,6 +452,26 @@ def more_measurements(pk, wl, torch, np, L):
         "gemm_phase_ms": round(t5g, 4), "gemm_phase_TFLOP/s": round(c5.flops / (t5g * 1e-3) / 1e12, 1),
         "gemm_phase_frac_of_fp8_mfma_peak": round(c5.flops / (t5g * 1e-3) / 1e12 / PEAK_TFLOPS["fp8"], 4),
         "reduce_phase_ms": round(t5r, 4), "reduce_phase_GB/s": round(red5 / (t5r * 1e-3) / 1e9, 1)}
+    # the same op with bf16 partial slots (the paper's element size for communicated tiles, s = 2): half the scatter and reduce traffic
+    part16 = part5.to(torch.bfloat16).view(torch.int16)
+    del part5
+    outg16 = outg5.view(torch.int16).reshape(-1)[:c5.P * mp5 * c5.N].view(c5.P, mp5, c5.N)
+
+    def rs5_16(phases):
+        def f():
+            if phases & 1:
+                ep[0] += 1
+            pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part16, outg16, fin5, fout5, ep[0], out5,
+                          phases, status, partial_dtype="bf16")
+        return f
+    t16 = timeit(rs5_16(pk.PHASE_ALL), n=10, w=4)
+    t16g = timeit(rs5_16(pk.PHASE_GEMM), n=10, w=4)
+    t16r = timeit(rs5_16(pk.PHASE_REDUCE), n=10, w=4)
+    bytes16 = 2 * c5.M * k5 + 2 * c5.M * c5.N * 2 + mp5 * c5.N * 2
+    out["cfg5_fp8_gemm_rs"]["bf16_partial_slots"] = {
+        "ms": round(t16, 4), "TFLOP/s": round(c5.flops / (t16 * 1e-3) / 1e12, 1), "gemm_phase_ms": round(t16g, 4),
+        "reduce_phase_ms": round(t16r, 4), "algorithmic_bytes": bytes16,
+        "frac_of_hbm_peak_on_its_own_bytes": round(bytes16 / (t16 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
     assert status[0].item() == 0, f"device status {status.tolist()}"
     return out
 
