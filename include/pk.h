@@ -224,7 +224,7 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
 
 /*
  * All-gather + GEMM for rank `rank` (paper section 4.1: first GEMM of the MLP, inputs sharded by rows are
- * gathered, weights column-sharded; section 3.1.3 "inter-SM overlapping": the chunks are moved by dedicated
+ * gathered, weights column-sharded; section 3.1.3, the paragraph on overlap across SMs: the chunks are moved by dedicated
  * communicator workers while the compute workers wait on a per-chunk flag before loading).
  *
  *   C_local = bf16( act( A_gathered . B_local ) )   (M x N/P; x scale_a*scale_b for fp8; act: pk_activation)
@@ -236,7 +236,7 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  *   C_local     M x N/P bf16
  *
  * Output tiles are scheduled chunk by chunk starting from the own chunk, then rank+1, rank+2, ... (mod P).
- * comm_cus (the paper's num_comm_sms, section 3.1.3 "SM partitioning", appendix D) is the number of compute
+ * comm_cus (the paper's num_comm_sms, section 3.1.3, the paragraph on partitioning the SMs, appendix D) is the number of compute
  * units this call leaves free for the communicator workgroups that move the chunks while it runs: the GEMM is
  * launched on the remaining ones (rounded down to a multiple of 8, at least 8).  0 = use every compute unit;
  * then the communicator must already be resident when this kernel starts, or the chunks must have landed.
@@ -338,7 +338,7 @@ pk_status pk_emu_deliver_partials(int P, int64_t M, int64_t N, int tile_m, int t
 pk_status pk_probe_mfma(int iters, int random_operands, uint64_t* report, double* flops_out /* host */, void* stream);
 
 /*
- * Compute-unit partition (paper section 3.1.3 "inter-SM overlapping" and its SM-partition study; appendix D
+ * Compute-unit partition (paper section 3.1.3, overlap across SMs and its SM-partition study; appendix D
  * num_comm_sms): creates two streams whose kernels run on disjoint sets of compute units, `comm_cus` of them
  * (a multiple of 8 in [8, #CU - 8], spread evenly over the 8 XCDs) for the communicator side and the rest for
  * the compute side.  Launch the communicator (here: pk_emu_deliver_*) on *comm_stream and pk_gemm_rs /
