@@ -34,6 +34,8 @@ def main():
                     help="untimed sustained run of the same step before the warm-up steps: the clock governor needs "
                          "~70 ms of load to settle (0 = measure the cold-start transient instead)")
     ap.add_argument("--extras", action="store_true", help="also time the phases alone and the live-arrival variants")
+    ap.add_argument("--serial-reduce", action="store_true",
+                    help="run the reduce of GEMM+RS after its GEMM instead of beside it (no PK_PHASE_OVERLAP)")
     ap.add_argument("--only-step", action="store_true",
                     help="time the step and nothing else (for profiler runs: no other launches of the same kernels)")
     args = ap.parse_args()
@@ -51,6 +53,7 @@ def main():
     pk.lib()                                            # fail loudly if the HIP library is missing
     rank = 0
     c3, c4 = wl.CONFIGS["cfg3"], wl.CONFIGS["cfg4"]
+    RS_PHASES = pk.PHASE_ALL | (0 if args.serial_reduce else pk.PHASE_OVERLAP)
 
     # ---------------- inputs (seeded, synthetic), uploaded once ----------------
     t0 = time.time()
@@ -80,6 +83,19 @@ def main():
     stream = torch.cuda.current_stream()
 
     def step(epoch, ev=None):
+        # the timed step: AG+GEMM, then GEMM+RS with its reduce hidden behind the GEMM (one call, PK_PHASE_OVERLAP)
+        if ev:
+            ev[0].record(stream)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, A4, B4, None, None, chunk_flags, epoch, C4, status)
+        if ev:
+            ev[1].record(stream)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, A3, B3, None, None, part, outgoing,
+                      flags_in, flags_out, epoch, out3, RS_PHASES, status)
+        if ev:
+            ev[2].record(stream)
+
+    def step_serial(epoch, ev=None):
+        # the same step with the two phases of GEMM+RS as calls of their own, one after the other: per-kernel durations
         if ev:
             ev[0].record(stream)
         pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, A4, B4, None, None, chunk_flags, epoch, C4, status)
@@ -125,7 +141,7 @@ def main():
     for _ in range(args.warmup):
         epoch += 1
         step(epoch)
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -134,11 +150,25 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     assert status[0].item() == 0, f"device status {status.tolist()}"
-    st_words = [x & 0xFFFFFFFF for x in status.tolist()]      # timing report of the last GEMM launch (the cfg3 one)
 
     ms_step = wall * 1e3 / args.steps
-    per = [[e[i].elapsed_time(e[i + 1]) for e in evs] for i in range(3)]
-    k_ag, k_rs, k_red = (sum(x) / args.steps for x in per)
+    per_op = [[e[i].elapsed_time(e[i + 1]) for e in evs] for i in range(2)]
+    k_ag, op_rs = (sum(x) / args.steps for x in per_op)       # the cfg4 GEMM launch; the whole GEMM+RS call
+
+    # the same number of steps once more with the phases of GEMM+RS apart (not part of `value`): the cfg3 GEMM as one
+    # launch, the reduce kernel alone behind it
+    evs_s = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        epoch += 1
+        step_serial(epoch, evs_s[i])
+    torch.cuda.synchronize()
+    ms_step_serial = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert status[0].item() == 0, f"device status {status.tolist()}"
+    st_words = [x & 0xFFFFFFFF for x in status.tolist()]      # timing report of the last GEMM launch (the cfg3 one)
+    per = [[e[i].elapsed_time(e[i + 1]) for e in evs_s] for i in range(3)]
+    k_ag_serial, k_rs, k_red = (sum(x) / args.steps for x in per)
+    per[0] = per_op[0]                                        # the cfg4 kernel's durations come from the timed steps
 
     # the MFMA rate this chip sustains in a register-only loop: operands all 1.0, then random sign + mantissa
     # (data-dependent power lowers the clock); per-run context for the roofline fraction below
@@ -167,7 +197,9 @@ def main():
         "gemm_kernel<256,256,bf16,RS> (cfg3)": {"ms": k_rs, "TFLOP/s": c3.flops / (k_rs * 1e-3) / 1e12},
         "reduce_kernel<8> (cfg3)": {"ms": k_red, "GB/s": red_bytes / (k_red * 1e-3) / 1e9},
     }
-    dom = "gemm_kernel<256,256,bf16,RS> (cfg3)" if k_rs >= k_ag else "gemm_kernel<256,256,bf16,AG> (cfg4)"
+    # the kernel the roofline is quoted for is the cfg4 GEMM: one launch per timed step, bracketed by events there (the
+    # cfg3 GEMM runs as two launches beside the reduce in the timed steps; its single-launch duration is the serial one)
+    dom = "gemm_kernel<256,256,bf16,AG> (cfg4)"
     ach = kernels[dom]["TFLOP/s"]
     traffic = measured_traffic()
     roofline = {"bound": "mfma", "kernel": dom, "achieved": round(ach, 2), "peak": PEAK_TFLOPS["bf16"],
@@ -199,6 +231,10 @@ def main():
         "kernel_ms_median_min": {k: [round(sorted(x)[len(x) // 2], 4), round(min(x), 4)]
                                  for k, x in zip(kernels, per)},
         "frac_of_mfma_peak_whole_step": round(value / PEAK_TFLOPS["bf16"], 4),
+        "gemm_rs_call_ms_in_timed_steps": round(op_rs, 4),
+        "reduce_overlapped": bool(RS_PHASES & pk.PHASE_OVERLAP),
+        "ms_per_step_with_serial_reduce": round(ms_step_serial, 4),
+        "TFLOP/s_with_serial_reduce": round(flops / (ms_step_serial * 1e-3) / 1e12, 2),
         "preheat_ms": args.preheat_ms,
         "ms_per_step_first_5_steps_from_idle": round(cold_ms, 4),
         "in_kernel_clock_report_cfg3_gemm": {
@@ -307,15 +343,20 @@ def more_measurements(pk, wl, torch, np, L):
     Cg = torch.zeros((m, n), dtype=torch.int16, device="cuda")
     t_gemm = timeit(lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", L["A3"], L["B3"], None, None, None, 1, Cg, status))
 
-    def fused():
-        ep[0] += 1
-        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
-                      L["flags_in"], L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, status)
-    t_fused = timeit(fused)
+    def fused(phases):
+        def f():
+            ep[0] += 1
+            pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                          L["flags_in"], L["flags_out"], ep[0], L["out3"], phases, status)
+        return f
+    t_serial = timeit(fused(pk.PHASE_ALL))
+    t_fused = timeit(fused(pk.PHASE_ALL | pk.PHASE_OVERLAP))
     out["table3_style_cfg3"] = {"t_gemm_ms": round(t_gemm, 4), "t_fused_ms": round(t_fused, 4),
                                 "comm_ratio": round((t_fused - t_gemm) / t_fused, 4),
                                 "gemm_TFLOP/s": round(c3.flops / (t_gemm * 1e-3) / 1e12, 1),
-                                "fused_TFLOP/s": round(c3.flops / (t_fused * 1e-3) / 1e12, 1)}
+                                "fused_TFLOP/s": round(c3.flops / (t_fused * 1e-3) / 1e12, 1),
+                                "t_fused_serial_reduce_ms": round(t_serial, 4),
+                                "comm_ratio_serial_reduce": round((t_serial - t_gemm) / t_serial, 4)}
     del Cg
 
     # --- variants of the two GEMM kernels, each timed alone back to back on the same buffers ---
@@ -440,7 +481,8 @@ def more_measurements(pk, wl, torch, np, L):
             pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part5, outg5, fin5, fout5, ep[0], out5,
                           phases, status)
         return f
-    t5 = timeit(rs5(pk.PHASE_ALL), n=10, w=4)
+    t5s = timeit(rs5(pk.PHASE_ALL), n=10, w=4)
+    t5 = timeit(rs5(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=10, w=4)
     t5g = timeit(rs5(pk.PHASE_GEMM), n=10, w=4)
     t5r = timeit(rs5(pk.PHASE_REDUCE), n=10, w=4)
     bytes5 = 2 * c5.M * k5 + 2 * c5.M * c5.N * 4 + mp5 * c5.N * 2
@@ -449,6 +491,7 @@ def more_measurements(pk, wl, torch, np, L):
         "ms": round(t5, 4), "TFLOP/s": round(c5.flops / (t5 * 1e-3) / 1e12, 1),
         "roofline": {"bound": "hbm", "achieved": round(bytes5 / (t5 * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(bytes5 / (t5 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "algorithmic_bytes": bytes5, "traffic": None},
+        "ms_serial_reduce": round(t5s, 4),
         "gemm_phase_ms": round(t5g, 4), "gemm_phase_TFLOP/s": round(c5.flops / (t5g * 1e-3) / 1e12, 1),
         "gemm_phase_frac_of_fp8_mfma_peak": round(c5.flops / (t5g * 1e-3) / 1e12 / PEAK_TFLOPS["fp8"], 4),
         "reduce_phase_ms": round(t5r, 4), "reduce_phase_GB/s": round(red5 / (t5r * 1e-3) / 1e9, 1)}
@@ -464,7 +507,7 @@ def more_measurements(pk, wl, torch, np, L):
             pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part16, outg16, fin5, fout5, ep[0], out5,
                           phases, status, partial_dtype="bf16")
         return f
-    t16 = timeit(rs5_16(pk.PHASE_ALL), n=10, w=4)
+    t16 = timeit(rs5_16(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=10, w=4)   # (next to the fp8 kernel: falls back to the serial reduce)
     t16g = timeit(rs5_16(pk.PHASE_GEMM), n=10, w=4)
     t16r = timeit(rs5_16(pk.PHASE_REDUCE), n=10, w=4)
     bytes16 = 2 * c5.M * k5 + 2 * c5.M * c5.N * 2 + mp5 * c5.N * 2

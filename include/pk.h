@@ -96,6 +96,7 @@ typedef enum {
 #define PK_PHASE_REDUCE 2u   /* wait for the P partials of each own tile, sum, round, store */
 #define PK_PHASE_ALL    3u
 #define PK_PHASE_WAIT   4u   /* pk_gemm_ar only: wait until every rank's reduced rows have landed in out_full */
+#define PK_PHASE_OVERLAP 8u  /* pk_gemm_rs with both phases: the reduce runs beside the GEMM (see pk_gemm_rs) */
 #define PK_AR_ROWS      8    /* rows of out_full covered by one all-reduce ready flag (columns: tile_n) */
 
 /* Flag granularity and derived sizes for a problem; filled by the *_plan calls (host struct). */
@@ -150,7 +151,17 @@ const char* pk_status_str(int status);
  *
  * Requirements: M % P == 0, K % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), N % 8 == 0 (bf16) or
  * % 16 == 0 (fp8); M/P and N need not be multiples of the tile (edge tiles are partial).  Otherwise
- * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).  comm_cus: as for pk_ag_gemm below, the
+ * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).
+ * PK_PHASE_ALL | PK_PHASE_OVERLAP hides the reduce behind the GEMM (section 3.1.3: communication that runs beside the
+ * compute workers): the tiles of this rank's own block are computed first, in a launch of their own; the rest of the GEMM
+ * and the reduce then run side by side, the reduce on a second stream that the library keeps per device (created at the
+ * first such call on a device, default priority) and joins back into `stream` before the call's work counts as done
+ * there.  The reduce waits only for the own block (complete by then) and for the peers' flags, never for the second GEMM
+ * launch, so either may be placed first.  Results are bit-identical to the plain call.  The flag needs both phases
+ * (PK_ERR_ARG otherwise) and is ignored where it cannot help: when the own block takes every round of the schedule, and
+ * next to the 256x256 fp8 kernel with bf16 slots or P other than 2, 4, 8.  Calls with the flag from several host threads
+ * on one device are serialised while they enqueue.
+ * comm_cus: as for pk_ag_gemm below, the
  * number of compute units the GEMM phase leaves to communicator workgroups (0 = none).  partial_dt: element type of
  * `partials` and `outgoing` (PK_ERR_DTYPE if unknown).
  */

@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "pk_device.h"
 #include "pk_gemm.h"
@@ -39,23 +40,38 @@ struct ReduceArgs {
 // makes an acquire fence (a whole-L2 invalidate per workgroup) unnecessary.
 constexpr int kCoherentStream = 1 | 2 | 16;
 
-template <int PT, bool S16>   // PT > 0: compile-time P; PT == 0: runtime P.  S16: the slots hold bf16
+// PT > 0: compile-time P; PT == 0: runtime P.  S16: the slots hold bf16.  AR: all-reduce mode (the reduced rows are also
+// pushed to the other ranks and announced).  NARROW: 4 output elements per thread and pass instead of 8 (one 16-byte load
+// per slot in flight: under 48 registers), for launches that must fit beside a GEMM workgroup that leaves few registers.
+template <int PT, bool S16, bool AR, bool NARROW = false>
 __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
     const int tid = threadIdx.x;
+    const int P = PT > 0 ? PT : r.P;
     const int tile = blockIdx.x / r.sub;
     const int sb = blockIdx.x - tile * r.sub;
     const int tmi = tile / r.tiles_n, tc = tile - tmi * r.tiles_n;
-    const int P = PT > 0 ? PT : r.P;
 
     // wait (paper appendix C): one lane per source rank polls that rank's flag for this tile
     int late = 0;
-    if (tid < P) {
-        if (!flag_wait(r.flags_in + (int64_t)tid * r.flags_per_slot + tile, r.epoch, r.timeout_ticks)) {
-            report_timeout(r.status, (uint32_t)tile, 2u);
-            late = 1;
+    if constexpr (AR) {
+        if (tid < P) {
+            if (!flag_wait(r.flags_in + (int64_t)tid * r.flags_per_slot + tile, r.epoch, r.timeout_ticks)) {
+                report_timeout(r.status, (uint32_t)tile, 2u);
+                late = 1;
+            }
         }
+        if (__syncthreads_or(late)) return;      // the whole workgroup leaves together: it meets at a barrier below
+    } else {
+        // every wave polls for itself and decides with a ballot: this instantiation uses no LDS, not even the word a
+        // workgroup-wide vote takes, so that its workgroups fit on a compute unit whose LDS a GEMM workgroup holds whole
+        for (int p = tid & 63; p < P; p += 64) {
+            if (!flag_wait(r.flags_in + (int64_t)p * r.flags_per_slot + tile, r.epoch, r.timeout_ticks)) {
+                if (tid < 64) report_timeout(r.status, (uint32_t)tile, 2u);
+                late = 1;
+            }
+        }
+        if (__ballot(late) != 0) return;
     }
-    if (__syncthreads_or(late)) return;
 
     constexpr int SLOT_ELEM = S16 ? 2 : 4;
     // one buffer descriptor per slot (a slot stays below 4 GiB, all P together need not)
@@ -84,6 +100,25 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
             }
         }
     };
+    if constexpr (NARROW) {
+        static_assert(!NARROW || (!S16 && !AR && PT > 0), "the narrow form is built for fp32 slots, compile-time P, no all-reduce");
+        const int cpr4 = cpr * 2;
+        for (int idx = tid; idx < total * 2; idx += 256) {
+            const int rr = idx / cpr4, cc = idx - rr * cpr4;
+            const int64_t off = (int64_t)(row_start + rr) * r.n + col0 + cc * 4;
+            const uint32_t boff = (uint32_t)(off * 4);
+            f32x4 v[PT > 0 ? PT : 1];
+#pragma unroll
+            for (int p = 0; p < PT; ++p)
+                v[p] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(slot(p), boff, 0, kCoherentStream));
+            f32x4 sum = v[0];
+#pragma unroll
+            for (int p = 1; p < PT; ++p) sum += v[p];
+            bf16x4 o = {(__bf16)sum[0], (__bf16)sum[1], (__bf16)sum[2], (__bf16)sum[3]};
+            __builtin_nontemporal_store(o, (bf16x4*)(r.out + off));
+        }
+        return;
+    }
     for (int idx = tid; idx < total; idx += 256) {
         const int rr = idx / cpr, cc = idx - rr * cpr;
         const int64_t off = (int64_t)(row_start + rr) * r.n + col0 + cc * 8;
@@ -125,7 +160,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
         }
         bf16x8 o = {(__bf16)s0[0], (__bf16)s0[1], (__bf16)s0[2], (__bf16)s0[3],
                     (__bf16)s1[0], (__bf16)s1[1], (__bf16)s1[2], (__bf16)s1[3]};
-        if (r.ar_flags_in) {
+        if constexpr (AR) {
             // all-reduce: consumers find these rows through flags, so write through
             const i32x4 ov = __builtin_bit_cast(i32x4, o);
             store16_writethrough(r.out + off, ov);
@@ -135,7 +170,7 @@ __global__ __launch_bounds__(256) void reduce_kernel(const ReduceArgs r) {
             __builtin_nontemporal_store(o, (bf16x8*)(r.out + off));
         }
     }
-    if (r.ar_flags_in && row_start < r.rows) {
+    if (AR && row_start < r.rows) {
         // `signal` per destination for this 8-row block: every wave waits for its stores, then one lane per rank
         __builtin_amdgcn_s_waitcnt(PK_WAIT_VMCNT0);
         __syncthreads();
@@ -356,15 +391,34 @@ static pk_status launch_kernel(const GemmArgs& a, int grid, hipStream_t stream) 
     return hipGetLastError() == hipSuccess ? PK_OK : PK_ERR_HIP;
 }
 
+// workgroups of a launch that shares out no tile: one per compute unit left to the GEMM (a multiple of 8, so that
+// workgroup id mod 8 stays the XCD), or the fewest that finish in the same number of rounds (448 slots on 256 CUs: 2
+// rounds of 224)
+static int schedule_grid(int slots, int comm_cus) {
+    int grid = (num_cus() - comm_cus) / 8 * 8;
+    if (grid < 8) grid = 8;
+    const int rounds = (slots + grid - 1) / grid;
+    const int even = ((slots + rounds - 1) / rounds + 7) / 8 * 8;
+    return even < grid ? even : grid;
+}
+
+// A launch covers the tile slots of the rounds [rounds.first, rounds.last) of the whole schedule (a round = one slot per
+// workgroup); {0, -1} = all of them.  Launches of one schedule use the same grid.
+struct RoundRange {
+    int first, last;
+};
+
 template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
-static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream) {
+static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream,
+                             RoundRange rr = {0, -1}) {
     a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
     constexpr bool HAS_SK = !BT && (EPI == EPI_RS || EPI == EPI_AG);   // the stream-K tail is built for these
     int grid = (num_cus() - comm_cus) / 8 * 8;
     if (grid < 8) grid = 8;
     a.sk_dp_slots = slots;
     const int rem = slots % grid;
-    if (ws && HAS_SK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
+    const bool part = rr.last >= 0;
+    if (!part && ws && HAS_SK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
         // With a workspace every compute unit works to the end: whole rounds of tiles, then the k range of the left-over
         // tiles shared out evenly (448 slots on 256 CUs: 256 whole tiles, then 192 tiles as 256 pieces of 3/4 tile).
         if (ws_bytes < kWsFlagBytes + (size_t)grid * BM * BN * 4) return PK_ERR_ARG;
@@ -373,41 +427,43 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size
         a.ws_tiles = (char*)ws + kWsFlagBytes;
         if (a.ws_epoch == 0) a.ws_epoch = a.epoch;     // a caller's workspace follows the caller's epochs
     } else {
-        // the fewest workgroups that finish in the same number of rounds (448 slots on 256 CUs: 2 rounds of 224)
-        const int rounds = (slots + grid - 1) / grid;
-        const int even = ((slots + rounds - 1) / rounds + 7) / 8 * 8;
-        if (even < grid) grid = even;
+        grid = schedule_grid(slots, comm_cus);
+        if (part) {
+            a.slot0 = min(rr.first * grid, slots);
+            a.sk_dp_slots = min(rr.last * grid, slots);
+            if (a.slot0 >= a.sk_dp_slots) return PK_OK;
+        }
     }
     if constexpr (HAS_SK) {
-        if (a.sk_dp_slots != slots) return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, true>(a, grid, stream);
+        if (!part && a.sk_dp_slots != slots) return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, true>(a, grid, stream);
     }
     return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, false>(a, grid, stream);
 }
 
 template <int EPI>
 static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const TileCfg& tc, bool fp8,
-                               void* ws, size_t ws_bytes, hipStream_t stream, bool bt = false) {
+                               void* ws, size_t ws_bytes, hipStream_t stream, bool bt = false, RoundRange rr = {0, -1}) {
     if (bt) {
         // second operand stored k-contiguous: built for the two base epilogues only
         if constexpr (EPI == EPI_RS || EPI == EPI_AG) {
             // 128-byte k-tiles in a ring of 2 stages: a k-contiguous operand is fetched as one piece per row and k-tile, and
             // 64-byte pieces use half of every 128-byte line they touch (measured: 7% slower than the row-major path)
             if (tc.bm == 256)
-                return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream)
-                           : launch_gemm<256, 256, 2, 4, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream);
-            return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream)
-                       : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream);
+                return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
+                           : launch_gemm<256, 256, 2, 4, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
+            return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
+                       : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
         } else {
             return PK_ERR_ARG;
         }
     }
     if (tc.bm == 256) {
         // 8 waves, 64-byte k-tiles (32 bf16 or 64 fp8 of k) in a ring of 4 LDS stages
-        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
-                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
+        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
+                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
     }
-    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
-               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
+    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
+               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -489,6 +545,31 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, int random_o
 
 using namespace pk;
 
+// A second stream per device, with the two events that fork it from and join it to the caller's stream: the reduce
+// phase of pk_gemm_rs runs on it beside the rest of the GEMM (PK_PHASE_OVERLAP).  Created at the first such call on a
+// device and kept until the process ends; default priority.  `lock` serialises the callers' fork/join sequences.
+struct SideStream {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ready = false;
+};
+static std::mutex side_lock;
+static SideStream side_streams[64];
+
+static pk_status side_stream_of_device(SideStream** out) {   // call with side_lock held
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PK_ERR_HIP;
+    SideStream& h = side_streams[dev];
+    if (!h.ready) {
+        if (hipStreamCreateWithFlags(&h.stream, hipStreamNonBlocking) != hipSuccess) return PK_ERR_HIP;
+        if (hipEventCreateWithFlags(&h.fork, hipEventDisableTiming) != hipSuccess) return PK_ERR_HIP;
+        if (hipEventCreateWithFlags(&h.join, hipEventDisableTiming) != hipSuccess) return PK_ERR_HIP;
+        h.ready = true;
+    }
+    *out = &h;
+    return PK_OK;
+}
+
 struct AllReduceOut {
     uint16_t* bcast_out;
     uint32_t* ar_flags_in;
@@ -525,12 +606,27 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         return PK_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     const TileCfg tc = {pl.tile_m, pl.tile_n};
+    // Overlapped reduce: the GEMM is launched in two parts, the rounds that hold this rank's own block (scheduled first)
+    // and the rest; the reduce runs on the library's second stream beside the second part, with one workgroup per
+    // compute unit, small enough in registers to sit next to a GEMM workgroup.  It waits for nothing the second part
+    // produces, so whichever of the two the hardware places first, both finish.
+    bool overlap = (phases & PK_PHASE_OVERLAP) && do_gemm && do_reduce && !ar && !cols && P > 1;
+    int own_rounds = 0, all_rounds = 0;
+    // The 256x256 fp8 GEMM leaves 48 registers per lane beside its two waves per SIMD (32 with bf16 slots: too few), the
+    // bf16 one 96: the reduce kernel that runs next to the former is the narrow one, built for fp32 slots and P of 2, 4
+    // or 8 (otherwise no overlap there).
+    const bool narrow_reduce = fp8 && pl.tile_m == 256;
+    if (narrow_reduce && (bf16_slots || (P != 2 && P != 4 && P != 8))) overlap = false;
     // one shard (slot): rows x cols.  Scatter along rows: M/P x N; along the last dimension: M x N/P
     const int64_t rows = cols ? M : M / P;
     const int64_t slot_cols = cols ? N / P : N;
 
+    GemmArgs a = {};
+    auto gemm = [&](RoundRange rr) {
+        return bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, false, rr)
+                          : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, bt, rr);
+    };
     if (do_gemm) {
-        GemmArgs a = {};
         const int elem = fp8 ? 1 : 2;
         a.A = (const char*)A_local;
         a.B = (const char*)B_local;
@@ -549,6 +645,20 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
         a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
         a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);
+        if (overlap) {
+            // own block first, and the tile rows finished round by round: the own block is complete after own_rounds
+            const int grid = schedule_grid(a.wg_per_group, comm_cus);
+            const int band = a.band > 0 ? a.band : 1;
+            const int64_t own_tiles = ceil_div(pl.tiles_m, band) * band * (int64_t)a.tiles_n;
+            own_rounds = (int)ceil_div(own_tiles, grid);
+            all_rounds = (int)ceil_div(a.wg_per_group, grid);
+            if (own_rounds >= all_rounds) {
+                overlap = false;
+            } else {
+                a.round_major = 1;
+                a.row_rot = rank * pl.tiles_m;
+            }
+        }
         a.rank = rank;
         a.partials = partials;
         a.outgoing = outgoing;
@@ -561,8 +671,21 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.epoch = epoch;
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
-        st = bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s)
-                        : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, bt);
+        st = overlap ? gemm({0, own_rounds}) : gemm({0, -1});
+        if (st != PK_OK) return st;
+    }
+    std::unique_lock<std::mutex> side_guard(side_lock, std::defer_lock);
+    SideStream* side = nullptr;
+    hipStream_t reduce_stream = s;
+    if (overlap) {
+        side_guard.lock();
+        st = side_stream_of_device(&side);
+        if (st != PK_OK) return st;
+        if (hipEventRecord(side->fork, s) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess)
+            return PK_ERR_HIP;
+        reduce_stream = side->stream;
+        // the rest of the GEMM is enqueued before the reduce, so that it is first in line for the compute units
+        st = gemm({own_rounds, all_rounds});
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
@@ -576,7 +699,7 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         r.tile_m = pl.tile_m;
         r.tile_n = pl.tile_n;
         r.tiles_n = pl.tiles_n;
-        r.rows_sub = 8;                       // 8 rows x tile_n columns x P slots per workgroup
+        r.rows_sub = 8;                       // 8 rows x tile_n columns x P slots per work item
         r.sub = pl.tile_m / r.rows_sub;
         r.slot_elems = rows * slot_cols;
         r.flags_per_slot = pl.flags_per_slot;
@@ -590,20 +713,32 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
             r.ar_flags_out = ar->ar_flags_out;
             r.ar_flags_per_slot = ar->ar_flags_per_slot;
         }
-        const int grid = (int)(pl.flags_per_slot * r.sub);
-        auto launch = [&](auto s16) {
-            constexpr bool S16 = decltype(s16)::value;
+        const int grid = (int)(pl.flags_per_slot * r.sub);   // one workgroup per work item
+        hipStream_t s = reduce_stream;
+        auto launch = [&](auto s16, auto armode) {
+            constexpr bool S16 = decltype(s16)::value, AR = decltype(armode)::value;
             switch (P) {
-                case 1: hipLaunchKernelGGL((reduce_kernel<1, S16>), dim3(grid), dim3(256), 0, s, r); break;
-                case 2: hipLaunchKernelGGL((reduce_kernel<2, S16>), dim3(grid), dim3(256), 0, s, r); break;
-                case 4: hipLaunchKernelGGL((reduce_kernel<4, S16>), dim3(grid), dim3(256), 0, s, r); break;
-                case 8: hipLaunchKernelGGL((reduce_kernel<8, S16>), dim3(grid), dim3(256), 0, s, r); break;
-                default: hipLaunchKernelGGL((reduce_kernel<0, S16>), dim3(grid), dim3(256), 0, s, r); break;
+                case 1: hipLaunchKernelGGL((reduce_kernel<1, S16, AR>), dim3(grid), dim3(256), 0, s, r); break;
+                case 2: hipLaunchKernelGGL((reduce_kernel<2, S16, AR>), dim3(grid), dim3(256), 0, s, r); break;
+                case 4: hipLaunchKernelGGL((reduce_kernel<4, S16, AR>), dim3(grid), dim3(256), 0, s, r); break;
+                case 8: hipLaunchKernelGGL((reduce_kernel<8, S16, AR>), dim3(grid), dim3(256), 0, s, r); break;
+                default: hipLaunchKernelGGL((reduce_kernel<0, S16, AR>), dim3(grid), dim3(256), 0, s, r); break;
             }
         };
-        if (bf16_slots) launch(std::true_type{});
-        else launch(std::false_type{});
+        const bool ar_mode = r.ar_flags_in != nullptr;
+        if (overlap && narrow_reduce) {
+            switch (P) {
+                case 2: hipLaunchKernelGGL((reduce_kernel<2, false, false, true>), dim3(grid), dim3(256), 0, s, r); break;
+                case 4: hipLaunchKernelGGL((reduce_kernel<4, false, false, true>), dim3(grid), dim3(256), 0, s, r); break;
+                default: hipLaunchKernelGGL((reduce_kernel<8, false, false, true>), dim3(grid), dim3(256), 0, s, r); break;
+            }
+        } else if (bf16_slots) ar_mode ? launch(std::true_type{}, std::true_type{}) : launch(std::true_type{}, std::false_type{});
+        else ar_mode ? launch(std::false_type{}, std::true_type{}) : launch(std::false_type{}, std::false_type{});
         if (hipGetLastError() != hipSuccess) return PK_ERR_HIP;
+    }
+    if (overlap) {
+        if (hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(s, side->join, 0) != hipSuccess)
+            return PK_ERR_HIP;
     }
     return PK_OK;
 }
@@ -731,7 +866,8 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
                      void* partials, void* outgoing, uint32_t* flags_in, uint32_t* flags_out, uint32_t epoch,
                      void* out_shard, uint32_t phases, int comm_cus, int partial_dt, int b_layout, void* workspace,
                      size_t workspace_bytes, uint32_t* status, uint64_t timeout_us, void* stream) {
-    if (phases == 0 || (phases & ~PK_PHASE_ALL)) return PK_ERR_ARG;
+    if ((phases & PK_PHASE_ALL) == 0 || (phases & ~(PK_PHASE_ALL | PK_PHASE_OVERLAP))) return PK_ERR_ARG;
+    if ((phases & PK_PHASE_OVERLAP) && (phases & PK_PHASE_ALL) != PK_PHASE_ALL) return PK_ERR_ARG;
     if (!aligned16(workspace)) return PK_ERR_ALIGN;
     return gemm_rs_impl(P, rank, M, N, K, dt, A_local, B_local, scale_a, scale_b, partials, outgoing, flags_in,
                         flags_out, epoch, out_shard, nullptr, phases, comm_cus, partial_dt, false, workspace, workspace_bytes,

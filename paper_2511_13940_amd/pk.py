@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libpk.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_ALIGN, ERR_RANK, ERR_ARG, ERR_HIP, ERR_TIMEOUT = range(9)
 BF16, FP8_E4M3 = 0, 1
-PHASE_GEMM, PHASE_REDUCE, PHASE_ALL, PHASE_WAIT = 1, 2, 3, 4
+PHASE_GEMM, PHASE_REDUCE, PHASE_ALL, PHASE_WAIT, PHASE_OVERLAP = 1, 2, 3, 4, 8
 AR_ROWS = 8
 ACTIVATIONS = {"none": 0, "relu": 1, "gelu_tanh": 2, "silu": 3}
 PARTIAL_F32, PARTIAL_BF16 = 0, 1
