@@ -929,15 +929,20 @@ def extras(pk, wl, torch, np, L):
         fin_t[rank].zero_()
         fout_t = torch.zeros_like(fin_t)
 
-        def rs_t():
-            ept[0] += 1
-            pk.pk_gemm_rs(P8, rank, MN, MN, P8 * kl, "bf16", At, Bt, None, None, part_t, outg_t, fin_t, fout_t, ept[0], out_t,
-                          pk.PHASE_ALL, L["status"])
-        t_g = timeit(lambda: pk.pk_ag_gemm(1, 0, MN, MN, kl, "bf16", At, Bt, None, None, None, 1, C_t, L["status"]), n=5, w=2)
-        t_f = timeit(rs_t, n=5, w=2)
+        def rs_t(phases):
+            def f():
+                ept[0] += 1
+                pk.pk_gemm_rs(P8, rank, MN, MN, P8 * kl, "bf16", At, Bt, None, None, part_t, outg_t, fin_t, fout_t, ept[0], out_t,
+                              phases, L["status"])
+            return f
+        t_g = timeit(lambda: pk.pk_ag_gemm(1, 0, MN, MN, kl, "bf16", At, Bt, None, None, None, 1, C_t, L["status"]), n=5, w=3)
+        t_s = timeit(rs_t(pk.PHASE_ALL), n=5, w=3)
+        t_f = timeit(rs_t(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=5, w=3)
         fl = 2.0 * MN * MN * kl
         out["table3_paper_sizes"][f"K={kl}"] = {"gemm_ms": round(t_g, 3), "gemm_rs_ms": round(t_f, 3),
                                                 "comm_ratio": round((t_f - t_g) / t_f, 3),
+                                                "gemm_rs_serial_reduce_ms": round(t_s, 3),
+                                                "comm_ratio_serial_reduce": round((t_s - t_g) / t_s, 3),
                                                 "gemm_TFLOP/s": round(fl / (t_g * 1e-3) / 1e12, 1),
                                                 "gemm_rs_TFLOP/s": round(fl / (t_f * 1e-3) / 1e12, 1)}
         del At, Bt

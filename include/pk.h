@@ -153,7 +153,8 @@ const char* pk_status_str(int status);
  * % 16 == 0 (fp8); M/P and N need not be multiples of the tile (edge tiles are partial).  Otherwise
  * PK_ERR_SHAPE.  `phases` selects which part runs (PK_PHASE_ALL normally).
  * PK_PHASE_ALL | PK_PHASE_OVERLAP hides the reduce behind the GEMM (section 3.1.3: communication that runs beside the
- * compute workers): the tiles of this rank's own block are computed first, in a launch of their own; the rest of the GEMM
+ * compute workers): the tile rows of this rank's own block (with as many of the following ones as fill whole rounds of
+ * workgroups) are computed first, in a launch of their own; the rest of the GEMM
  * and the reduce then run side by side, the reduce on a second stream that the library keeps per device (created at the
  * first such call on a device, default priority) and joins back into `stream` before the call's work counts as done
  * there.  The reduce waits only for the own block (complete by then) and for the peers' flags, never for the second GEMM

@@ -76,12 +76,9 @@ struct GemmArgs {
     // stream-K tail: the first sk_dp_slots tile slots are computed whole, one per workgroup and round; the k range of the
     // remaining ones is shared out evenly (sk_dp_slots = all slots: no such tail)
     int32_t sk_dp_slots;
-    // a launch may cover the slots [slot0, sk_dp_slots) only (the others belong to another launch with the same grid)
-    int32_t slot0;
-    // round_major: the slots of one round of the launch (gridDim.x consecutive ones) are gridDim.x consecutive tiles, an
-    // eighth of them per XCD, so that the tile rows finish in order, round by round; otherwise every XCD keeps one
-    // contiguous eighth of the whole tile range over all rounds.  row_rot: the tile row that is scheduled first.
-    int32_t round_major, row_rot;
+    // A launch may cover a range of the problem's tile rows only: its groups span n_groups * grp_tile_rows rows that start
+    // at tile row row_rot and wrap around at all_tile_rows (0 = the groups cover every row, no rotation).
+    int32_t row_rot, all_tile_rows;
     char* ws_tiles;           // [gridDim.x] raw accumulator tiles of BM * BN fp32 (a workgroup's piece that does not start a tile)
     uint32_t* ws_flags;       // [gridDim.x] ready flags of those pieces (ws_epoch)
     uint32_t ws_epoch;
@@ -272,7 +269,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
     uint32_t n_tiles_done = 0;
     uint64_t seen_chunks = 1ull << (g.rank & 63);
     const uint64_t all_chunks = g.k_chunks >= 64 ? ~0ull : (1ull << g.k_chunks) - 1;
-    int v = g.slot0 + blockIdx.x;
+    int v = blockIdx.x;
     // EPI_AG: a slot whose chunk has not landed when it is first visited is put aside (bit i = this workgroup's i-th slot)
     // and taken up again, now waiting, once the workgroup has gone through its other slots: tiles of chunks that are
     // already there never queue behind a late one.  Slots beyond the 64th wait on the spot.
@@ -332,14 +329,7 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             }
             const int gi = slot / g.wg_per_group;
             const int u = slot - gi * g.wg_per_group;
-            int t;
-            if (g.round_major) {
-                const int rnd = u / (int)gridDim.x, pos = u - rnd * (int)gridDim.x;
-                const int in_round = min((int)gridDim.x, g.wg_per_group - rnd * (int)gridDim.x);
-                t = rnd * (int)gridDim.x + (pos & 7) * (in_round >> 3) + (pos >> 3);
-            } else {
-                t = (u & 7) * (g.wg_per_group >> 3) + (u >> 3);
-            }
+            const int t = (u & 7) * (g.wg_per_group >> 3) + (u >> 3);
             if (t >= G) continue;
             const int BAND = g.band > 0 ? g.band : 1;
             const int band = t / (BAND * g.tiles_n);
@@ -349,8 +339,11 @@ __global__ __launch_bounds__(64 * WM * WN, 1) void gemm_kernel(const GemmArgs g)
             const int tr = band * BAND + (rem - tc * rows_in_band);
             int grp = g.group0 + gi;
             if (grp >= g.n_groups) grp -= g.n_groups;
-            int tile_row = grp * g.grp_tile_rows + tr + g.row_rot;
-            if (tile_row >= g.n_groups * g.grp_tile_rows) tile_row -= g.n_groups * g.grp_tile_rows;
+            int tile_row = grp * g.grp_tile_rows + tr;
+            if (g.all_tile_rows > 0) {
+                tile_row += g.row_rot;
+                if (tile_row >= g.all_tile_rows) tile_row -= g.all_tile_rows;
+            }
             q = tile_row / g.tiles_m_shard;              // destination rank (RS) / source chunk (AG)
             tmi = tile_row - q * g.tiles_m_shard;
             row0 = q * g.rows_per_shard + tmi * BM;

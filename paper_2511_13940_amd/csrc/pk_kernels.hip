@@ -402,23 +402,15 @@ static int schedule_grid(int slots, int comm_cus) {
     return even < grid ? even : grid;
 }
 
-// A launch covers the tile slots of the rounds [rounds.first, rounds.last) of the whole schedule (a round = one slot per
-// workgroup); {0, -1} = all of them.  Launches of one schedule use the same grid.
-struct RoundRange {
-    int first, last;
-};
-
 template <int BM, int BN, int WM, int WN, int KB, int NS, bool FP8, int EPI, bool BT = false>
-static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream,
-                             RoundRange rr = {0, -1}) {
+static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size_t ws_bytes, hipStream_t stream) {
     a.ktiles = a.ktiles * 128 / KB;          // callers count k-tiles of 128 bytes
     constexpr bool HAS_SK = !BT && (EPI == EPI_RS || EPI == EPI_AG);   // the stream-K tail is built for these
     int grid = (num_cus() - comm_cus) / 8 * 8;
     if (grid < 8) grid = 8;
     a.sk_dp_slots = slots;
     const int rem = slots % grid;
-    const bool part = rr.last >= 0;
-    if (!part && ws && HAS_SK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
+    if (ws && HAS_SK && slots > grid && rem != 0 && a.ktiles >= 8 * NS && grid <= (int)(kWsFlagBytes / 4)) {
         // With a workspace every compute unit works to the end: whole rounds of tiles, then the k range of the left-over
         // tiles shared out evenly (448 slots on 256 CUs: 256 whole tiles, then 192 tiles as 256 pieces of 3/4 tile).
         if (ws_bytes < kWsFlagBytes + (size_t)grid * BM * BN * 4) return PK_ERR_ARG;
@@ -428,42 +420,37 @@ static pk_status launch_gemm(GemmArgs a, int slots, int comm_cus, void* ws, size
         if (a.ws_epoch == 0) a.ws_epoch = a.epoch;     // a caller's workspace follows the caller's epochs
     } else {
         grid = schedule_grid(slots, comm_cus);
-        if (part) {
-            a.slot0 = min(rr.first * grid, slots);
-            a.sk_dp_slots = min(rr.last * grid, slots);
-            if (a.slot0 >= a.sk_dp_slots) return PK_OK;
-        }
     }
     if constexpr (HAS_SK) {
-        if (!part && a.sk_dp_slots != slots) return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, true>(a, grid, stream);
+        if (a.sk_dp_slots != slots) return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, true>(a, grid, stream);
     }
     return launch_kernel<BM, BN, WM, WN, KB, NS, FP8, EPI, BT, false>(a, grid, stream);
 }
 
 template <int EPI>
 static pk_status dispatch_gemm(const GemmArgs& a, int slots, int comm_cus, const TileCfg& tc, bool fp8,
-                               void* ws, size_t ws_bytes, hipStream_t stream, bool bt = false, RoundRange rr = {0, -1}) {
+                               void* ws, size_t ws_bytes, hipStream_t stream, bool bt = false) {
     if (bt) {
         // second operand stored k-contiguous: built for the two base epilogues only
         if constexpr (EPI == EPI_RS || EPI == EPI_AG) {
             // 128-byte k-tiles in a ring of 2 stages: a k-contiguous operand is fetched as one piece per row and k-tile, and
             // 64-byte pieces use half of every 128-byte line they touch (measured: 7% slower than the row-major path)
             if (tc.bm == 256)
-                return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
-                           : launch_gemm<256, 256, 2, 4, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
-            return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
-                       : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
+                return fp8 ? launch_gemm<256, 256, 2, 4, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream)
+                           : launch_gemm<256, 256, 2, 4, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream);
+            return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream)
+                       : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI, true>(a, slots, comm_cus, ws, ws_bytes, stream);
         } else {
             return PK_ERR_ARG;
         }
     }
     if (tc.bm == 256) {
         // 8 waves, 64-byte k-tiles (32 bf16 or 64 fp8 of k) in a ring of 4 LDS stages
-        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
-                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
+        return fp8 ? launch_gemm<256, 256, 2, 4, 64, 4, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
+                   : launch_gemm<256, 256, 2, 4, 64, 4, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
     }
-    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr)
-               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream, rr);
+    return fp8 ? launch_gemm<128, 128, 2, 2, 128, 2, true, EPI>(a, slots, comm_cus, ws, ws_bytes, stream)
+               : launch_gemm<128, 128, 2, 2, 128, 2, false, EPI>(a, slots, comm_cus, ws, ws_bytes, stream);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -606,12 +593,12 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         return PK_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     const TileCfg tc = {pl.tile_m, pl.tile_n};
-    // Overlapped reduce: the GEMM is launched in two parts, the rounds that hold this rank's own block (scheduled first)
-    // and the rest; the reduce runs on the library's second stream beside the second part, with one workgroup per
-    // compute unit, small enough in registers to sit next to a GEMM workgroup.  It waits for nothing the second part
-    // produces, so whichever of the two the hardware places first, both finish.
+    // Overlapped reduce: the GEMM is launched in two parts, the tile rows of this rank's own block (plus as many of the
+    // next ranks' as fill whole rounds) and the rest; the reduce runs on the library's second stream beside the second
+    // part: its workgroups use no LDS and few enough registers to sit next to a GEMM workgroup.  It waits for nothing
+    // the second part produces, so whichever of the two the hardware places first, both finish.
     bool overlap = (phases & PK_PHASE_OVERLAP) && do_gemm && do_reduce && !ar && !cols && P > 1;
-    int own_rounds = 0, all_rounds = 0;
+    int first_rows = 0;                      // tile rows of the first part (0: one launch for everything)
     // The 256x256 fp8 GEMM leaves 48 registers per lane beside its two waves per SIMD (32 with bf16 slots: too few), the
     // bf16 one 96: the reduce kernel that runs next to the former is the narrow one, built for fp32 slots and P of 2, 4
     // or 8 (otherwise no overlap there).
@@ -622,9 +609,18 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     const int64_t slot_cols = cols ? N / P : N;
 
     GemmArgs a = {};
-    auto gemm = [&](RoundRange rr) {
-        return bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, false, rr)
-                          : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, bt, rr);
+    const int all_rows = cols ? pl.tiles_m : P * pl.tiles_m;     // tile rows of the whole local product
+    const int tiles_n_all = cols ? P * pl.tiles_n : pl.tiles_n;
+    // one launch over `n_rows` tile rows that start at tile row `row0` (wrapping around at all_rows)
+    auto gemm = [&](int row0, int n_rows) {
+        a.grp_tile_rows = n_rows;
+        a.row_rot = row0;
+        a.all_tile_rows = (row0 == 0 && n_rows == all_rows) ? 0 : all_rows;
+        const int64_t G = (int64_t)n_rows * a.tiles_n;
+        a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
+        a.band = pick_band(n_rows, a.tiles_n, a.wg_per_group / 8);
+        return bf16_slots ? dispatch_gemm<EPI_RS16>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s)
+                          : dispatch_gemm<EPI_RS>(a, a.wg_per_group, comm_cus, tc, fp8, ws, ws_bytes, s, bt);
     };
     if (do_gemm) {
         const int elem = fp8 ? 1 : 2;
@@ -636,28 +632,31 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.ktiles = (int32_t)(pl.local_k / (fp8 ? 128 : 64));
         a.rows_per_shard = (int32_t)rows;
         a.tiles_m_shard = pl.tiles_m;
-        a.tiles_n = cols ? P * pl.tiles_n : pl.tiles_n;
-        a.grp_tile_rows = cols ? pl.tiles_m : P * pl.tiles_m;
+        a.tiles_n = tiles_n_all;
         a.cols_per_shard = cols ? (int32_t)slot_cols : 0;
         a.tiles_n_shard = cols ? pl.tiles_n : 0;
         a.n_groups = 1;
         a.group0 = 0;
-        const int64_t G = (int64_t)a.grp_tile_rows * a.tiles_n;
-        a.wg_per_group = (int32_t)(8 * ceil_div(G, 8));
-        a.band = pick_band(a.grp_tile_rows, a.tiles_n, a.wg_per_group / 8);
         if (overlap) {
-            // own block first, and the tile rows finished round by round: the own block is complete after own_rounds
-            const int grid = schedule_grid(a.wg_per_group, comm_cus);
-            const int band = a.band > 0 ? a.band : 1;
-            const int64_t own_tiles = ceil_div(pl.tiles_m, band) * band * (int64_t)a.tiles_n;
-            own_rounds = (int)ceil_div(own_tiles, grid);
-            all_rounds = (int)ceil_div(a.wg_per_group, grid);
-            if (own_rounds >= all_rounds) {
-                overlap = false;
-            } else {
-                a.round_major = 1;
-                a.row_rot = rank * pl.tiles_m;
+            // The first part: the own block's rows rounded up to whole bands of 4, then as many more bands (up to 7) as
+            // waste the least of its last round.  No second part left: one launch, reduce afterwards.
+            int grid = (num_cus() - comm_cus) / 8 * 8;
+            if (grid < 8) grid = 8;
+            const int band = 4;
+            int best = 0;
+            double best_waste = 2.0;
+            for (int k = 0; k < 8; ++k) {
+                const int r1 = (int)ceil_div(pl.tiles_m, band) * band + k * band;
+                if (r1 >= all_rows) break;
+                const int64_t t1 = (int64_t)r1 * tiles_n_all;
+                const double waste = (double)(ceil_div(t1, grid) * grid - t1) / grid + 0.02 * k;
+                if (waste < best_waste) {
+                    best_waste = waste;
+                    best = r1;
+                }
             }
+            first_rows = best;
+            if (first_rows == 0) overlap = false;
         }
         a.rank = rank;
         a.partials = partials;
@@ -671,7 +670,7 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
         a.epoch = epoch;
         a.status = status;
         a.timeout_ticks = timeout_ticks(timeout_us);
-        st = overlap ? gemm({0, own_rounds}) : gemm({0, -1});
+        st = overlap ? gemm(rank * pl.tiles_m, first_rows) : gemm(0, all_rows);
         if (st != PK_OK) return st;
     }
     std::unique_lock<std::mutex> side_guard(side_lock, std::defer_lock);
@@ -685,7 +684,7 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
             return PK_ERR_HIP;
         reduce_stream = side->stream;
         // the rest of the GEMM is enqueued before the reduce, so that it is first in line for the compute units
-        st = gemm({own_rounds, all_rounds});
+        st = gemm((rank * pl.tiles_m + first_rows) % all_rows, all_rows - first_rows);
         if (st != PK_OK) return st;
     }
     if (do_reduce) {
