@@ -60,3 +60,51 @@ def test_captured_mlp_block_replays_bit_identically():
         assert torch.equal(out, want_out), f"replay {i}"
         assert torch.isfinite(scratch)
     assert torch.all(flags_in[rank] == 3) and torch.all(flags_out[(rank + 1) % P] == 3)
+
+
+def test_captured_gemm_rs_with_the_reduce_beside_the_gemm_replays_bit_identically():
+    """PK_PHASE_OVERLAP forks to the library's second stream and joins it back: inside a capture that stream becomes part
+    of the graph.  The library's stream and events exist from the eager call on."""
+    P, rank, M, N, K = 4, 1, 4096, 2048, 1024          # 512 tiles of 128: the own block's rows and the rest, two launches
+    inp = wl.gemm_rs_inputs(P, M, N, K, "bf16", rank, seed=53)
+    A, B = hz.elem_view(inp["A_local"], "bf16"), hz.elem_view(inp["B_local"], "bf16")
+    plan = pk.pk_gemm_rs_plan(P, M, N, K, "bf16")
+    mp = M // P
+    part = hz.dev(inp["partials"])
+    outgoing = torch.zeros((P, mp, N), dtype=torch.float32, device="cuda")
+    flags_in = torch.full((P, plan.flags_per_slot), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+    flags_in[rank].zero_()
+    flags_out = torch.zeros_like(flags_in)
+    out = torch.zeros((mp, N), dtype=torch.int16, device="cuda")
+    status = torch.zeros(8, dtype=torch.int32, device="cuda")
+
+    def op(epoch, phases):
+        pk.pk_gemm_rs(P, rank, M, N, K, "bf16", A, B, None, None, part, outgoing, flags_in, flags_out, epoch, out, phases,
+                      status)
+
+    op(1, pk.PHASE_ALL)
+    torch.cuda.synchronize()
+    want = out.clone()
+    op(2, pk.PHASE_ALL | pk.PHASE_OVERLAP)             # eager: creates the library's second stream
+    torch.cuda.synchronize()
+    assert status[0].item() == 0 and torch.equal(out, want)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        op(3, pk.PHASE_ALL | pk.PHASE_OVERLAP)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            op(4, pk.PHASE_ALL | pk.PHASE_OVERLAP)
+    torch.cuda.synchronize()
+    for i in range(4):
+        out.fill_(-1)
+        part[rank].fill_(float("nan"))
+        scratch = torch.randn(1 << 20, device="cuda").sum()      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert status[0].item() == 0
+        assert torch.equal(out, want), f"replay {i}"
+        assert torch.isfinite(scratch)
+    assert torch.all(flags_in[rank] == 4)
