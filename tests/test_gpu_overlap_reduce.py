@@ -75,3 +75,33 @@ def test_overlap_flag_needs_both_phases():
         with pytest.raises(pk.PkError) as e:
             pk.pk_gemm_rs(2, 0, 256, 256, 512, "bf16", t, t, None, None, t, t, t, t, 1, t, phases, t)
         assert e.value.code == pk.ERR_ARG
+
+
+def test_overlap_on_a_compute_unit_partition_with_live_peers():
+    """The GEMM launches on the compute stream of a partition (224 workgroups), the peers' partials arrive through the
+    communicator stream while it runs, the reduce on the library's own stream: same bits as the plain pre-landed call."""
+    P, rank, M, N, K = 4, 3, 4096, 4096, 4 * 256
+    inp = wl.gemm_rs_inputs(P, M, N, K, "bf16", rank, seed=21)
+    base = hz.run_gemm_rs(P, rank, M, N, K, "bf16", inp["A_local"], inp["B_local"], inp["partials"])
+    check_rs(P, rank, "bf16", inp, base, K // P)
+    comp, comm = pk.pk_partition_create(32)
+    try:
+        for i, n_wg in enumerate([32, 128]):
+            order = wl.arrival_order(P, rank, "random", seed=i)
+            res = hz.run_gemm_rs(P, rank, M, N, K, "bf16", inp["A_local"], inp["B_local"], inp["partials"], deliver="emu",
+                                 order=order, epoch=i + 1, comm_cus=32, n_wg=n_wg, partition=(comp, comm), phases=OVERLAP,
+                                 timeout_us=2_000_000)
+            assert res["status"][0] == 0
+            assert np.array_equal(res["out_bits"], base["out_bits"])
+            for q in range(P):
+                if q != rank:
+                    assert np.array_equal(res["outgoing"][q].view(np.uint32), base["outgoing"][q].view(np.uint32))
+    finally:
+        torch.cuda.synchronize()
+        pk.pk_partition_destroy(comp, comm)
+
+
+def test_overlap_flag_with_a_single_rank_is_the_plain_gemm():
+    inp = wl.gemm_rs_inputs(1, 1024, 2048, 512, "bf16", 0, seed=4)
+    res = hz.run_gemm_rs(1, 0, 1024, 2048, 512, "bf16", inp["A_local"], inp["B_local"], inp["partials"], phases=OVERLAP)
+    check_rs(1, 0, "bf16", inp, res, 512)
