@@ -419,7 +419,7 @@ def more_measurements(pk, wl, torch, np, L):
         pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_live, ep[0], L["C4"],
                       status, comm_cus=COMM, stream=comp)
         comp.wait_stream(side)
-    t_ag_live = timeit(ag_live, st=comp)
+    t_ag_live = timeit(ag_live, w=30, st=comp)
     t_ag_pre = timeit(lambda: pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None,
                                             L["chunk_flags"], 1, L["C4"], status, comm_cus=COMM, stream=comp), st=comp)
     flags_live3 = torch.zeros_like(L["flags_in"])
@@ -436,7 +436,7 @@ def more_measurements(pk, wl, torch, np, L):
         pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
                       flags_live3, L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, status, comm_cus=COMM, stream=comp)
         comp.wait_stream(side)
-    t_rs_live = timeit(rs_live, st=comp)
+    t_rs_live = timeit(rs_live, w=30, st=comp)
 
     def rs_pre():
         ep[0] += 1
@@ -445,6 +445,40 @@ def more_measurements(pk, wl, torch, np, L):
     t_rs_pre = timeit(rs_pre, st=comp)
     torch.cuda.synchronize()
     pk.pk_partition_destroy(h_comp, h_comm)
+
+    # --- live arrival without a partition: the op on every compute unit, the communicator's workgroups (no LDS, under 64
+    # registers) resident beside the GEMM's on the same compute units, on a second stream ---
+    side2 = torch.cuda.Stream()
+
+    def ag_live_beside():
+        ep[0] += 1
+        done.record(stream)
+        side2.wait_event(done)
+        with torch.cuda.stream(side2):
+            counters.zero_()
+        pk.pk_emu_deliver_chunks(c4.P, c4.M, c4.K, 2, staging, L["A4"], flags_live, ep[0], order, 0, counters,
+                                 stream=side2, n_wg=256)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None, flags_live, ep[0], L["C4"], status)
+        stream.wait_stream(side2)
+    t_ag_beside = timeit(ag_live_beside, w=30)      # (a longer warm-up: this mix of kernels settles at its own clock)
+    t_ag_pre_all = timeit(lambda: pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, L["A4"], L["B4"], None, None,
+                                                L["chunk_flags"], 1, L["C4"], status))
+
+    def rs_live_beside():
+        ep[0] += 1
+        done.record(stream)
+        side2.wait_event(done)
+        pk.pk_emu_deliver_partials(c3.P, c3.M, c3.N, p3.tile_m, p3.tile_n, stage3, L["part"], flags_live3, ep[0],
+                                   peers, 0, stream=side2, n_wg=512)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
+                      flags_live3, L["flags_out"], ep[0], L["out3"], pk.PHASE_ALL, status)
+        stream.wait_stream(side2)
+    t_rs_beside = timeit(rs_live_beside, w=30)
+    out["live_arrival_no_partition"] = {
+        "ag_gemm_cfg4": {"t_fused_live_ms": round(t_ag_beside, 4), "t_fused_prelanded_ms": round(t_ag_pre_all, 4),
+                         "live_over_prelanded": round(t_ag_beside / t_ag_pre_all, 3), "communicator_workgroups": 256},
+        "gemm_rs_cfg3": {"t_fused_live_ms": round(t_rs_beside, 4), "t_fused_prelanded_ms": round(t_serial, 4),
+                         "live_over_prelanded": round(t_rs_beside / t_serial, 3), "communicator_workgroups": 512}}
     out["live_arrival"] = {
         "comm_cus": COMM,
         "ag_gemm_cfg4": {"t_fused_live_ms": round(t_ag_live, 4), "t_fused_prelanded_same_partition_ms": round(t_ag_pre, 4),

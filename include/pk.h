@@ -250,8 +250,9 @@ pk_status pk_gemm_ar(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  * Output tiles are scheduled chunk by chunk starting from the own chunk, then rank+1, rank+2, ... (mod P).
  * comm_cus (the paper's num_comm_sms, section 3.1.3, the paragraph on partitioning the SMs, appendix D) is the number of compute
  * units this call leaves free for the communicator workgroups that move the chunks while it runs: the GEMM is
- * launched on the remaining ones (rounded down to a multiple of 8, at least 8).  0 = use every compute unit;
- * then the communicator must already be resident when this kernel starts, or the chunks must have landed.
+ * launched on the remaining ones (rounded down to a multiple of 8, at least 8).  0 = use every compute unit:
+ * communicator workgroups then run only where they fit beside a GEMM workgroup (it holds all of the compute unit's LDS
+ * and leaves 80 registers per lane, bf16, or 48, fp8) or where the schedule leaves a compute unit empty.
  * Requirements: M % P == 0, N % P == 0, K % 64 == 0 (bf16) or % 128 == 0 (fp8), (N/P) % 8 == 0 (bf16) or
  * % 16 == 0 (fp8).  With P == 1 this is a plain GEMM with bf16 output (chunk_flags may then be NULL).
  */
