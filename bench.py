@@ -34,6 +34,8 @@ def main():
                     help="untimed sustained run of the same step before the warm-up steps: the clock governor needs "
                          "~70 ms of load to settle (0 = measure the cold-start transient instead)")
     ap.add_argument("--extras", action="store_true", help="also time the phases alone and the live-arrival variants")
+    ap.add_argument("--buffer-sets", type=int, default=3,
+                    help="copies of every operand, partial-slot and output buffer that the timed steps rotate through")
     ap.add_argument("--serial-reduce", action="store_true",
                     help="run the reduce of GEMM+RS after its GEMM instead of beside it (no PK_PHASE_OVERLAP)")
     ap.add_argument("--only-step", action="store_true",
@@ -81,32 +83,42 @@ def main():
     chunk_flags = torch.full((c4.P,), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
     status = torch.zeros(8, dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream()
+    # Buffer sets the steps rotate through (step e uses set e mod n), so that no step finds its operands, slots or outputs
+    # where the same step left them: set 0 is the tensors above, the others are copies (about 1 GB each, four times the
+    # 256 MB Infinity Cache already).
+    names = ("A3", "B3", "part", "outgoing", "out3", "flags_in", "flags_out", "A4", "B4", "C4")
+    here = locals()
+    sets = [{k: here[k] for k in names}]
+    for _ in range(max(args.buffer_sets, 1) - 1):
+        sets.append({k: v.clone() for k, v in sets[0].items()})
 
     def step(epoch, ev=None):
         # the timed step: AG+GEMM, then GEMM+RS with its reduce hidden behind the GEMM (one call, PK_PHASE_OVERLAP)
+        S = sets[epoch % len(sets)]
         if ev:
             ev[0].record(stream)
-        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, A4, B4, None, None, chunk_flags, epoch, C4, status)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, S["A4"], S["B4"], None, None, chunk_flags, epoch, S["C4"], status)
         if ev:
             ev[1].record(stream)
-        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, A3, B3, None, None, part, outgoing,
-                      flags_in, flags_out, epoch, out3, RS_PHASES, status)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, S["A3"], S["B3"], None, None, S["part"], S["outgoing"],
+                      S["flags_in"], S["flags_out"], epoch, S["out3"], RS_PHASES, status)
         if ev:
             ev[2].record(stream)
 
     def step_serial(epoch, ev=None):
         # the same step with the two phases of GEMM+RS as calls of their own, one after the other: per-kernel durations
+        S = sets[epoch % len(sets)]
         if ev:
             ev[0].record(stream)
-        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, A4, B4, None, None, chunk_flags, epoch, C4, status)
+        pk.pk_ag_gemm(c4.P, rank, c4.M, c4.N, c4.K, c4.dtype, S["A4"], S["B4"], None, None, chunk_flags, epoch, S["C4"], status)
         if ev:
             ev[1].record(stream)
-        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, A3, B3, None, None, part, outgoing,
-                      flags_in, flags_out, epoch, out3, pk.PHASE_GEMM, status)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, S["A3"], S["B3"], None, None, S["part"], S["outgoing"],
+                      S["flags_in"], S["flags_out"], epoch, S["out3"], pk.PHASE_GEMM, status)
         if ev:
             ev[2].record(stream)
-        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, None, None, None, None, part, None,
-                      flags_in, None, epoch, out3, pk.PHASE_REDUCE, status)
+        pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, None, None, None, None, S["part"], None,
+                      S["flags_in"], None, epoch, S["out3"], pk.PHASE_REDUCE, status)
         if ev:
             ev[3].record(stream)
 
@@ -169,6 +181,24 @@ def main():
     per = [[e[i].elapsed_time(e[i + 1]) for e in evs_s] for i in range(3)]
     k_ag_serial, k_rs, k_red = (sum(x) / args.steps for x in per)
     per[0] = per_op[0]                                        # the cfg4 kernel's durations come from the timed steps
+
+    # and once more on one buffer set only (every step finds what the Infinity Cache kept of the step before): cache-warm
+    ms_step_one_set = None
+    if len(sets) > 1:
+        rotating, sets = sets, sets[:1]
+        for _ in range(args.warmup):
+            epoch += 1
+            step(epoch)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            epoch += 1
+            step(epoch)
+        torch.cuda.synchronize()
+        ms_step_one_set = (time.perf_counter() - t0) * 1e3 / args.steps
+        sets = rotating
+        del rotating
+    sets = sets[:1]                                           # the copies are not needed any more
 
     # the MFMA rate this chip sustains in a register-only loop: operands all 1.0, then random sign + mantissa
     # (data-dependent power lowers the clock); per-run context for the roofline fraction below
@@ -236,6 +266,8 @@ def main():
         "ms_per_step_with_serial_reduce": round(ms_step_serial, 4),
         "TFLOP/s_with_serial_reduce": round(flops / (ms_step_serial * 1e-3) / 1e12, 2),
         "preheat_ms": args.preheat_ms,
+        "buffer_sets_rotated": max(args.buffer_sets, 1),
+        "ms_per_step_one_buffer_set_cache_warm": round(ms_step_one_set, 4) if ms_step_one_set else None,
         "ms_per_step_first_5_steps_from_idle": round(cold_ms, 4),
         "in_kernel_clock_report_cfg3_gemm": {
             "core_clock_MHz": round(100.0 * st_words[5] / max(st_words[4], 1)),
