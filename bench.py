@@ -184,7 +184,7 @@ def main():
 
     # and once more on one buffer set only (every step finds what the Infinity Cache kept of the step before): cache-warm
     ms_step_one_set = None
-    if len(sets) > 1:
+    if len(sets) > 1 and not args.only_step:
         rotating, sets = sets, sets[:1]
         for _ in range(args.warmup):
             epoch += 1
