@@ -190,7 +190,7 @@ pk_status pk_gemm_rs(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype 
  *
  * Requirements: K % P == 0, N % P == 0, (K/P) % 64 == 0 (bf16) or % 128 == 0 (fp8), (N/P) % 8 == 0 (bf16) or % 16 == 0
  * (fp8); M is arbitrary; M and N/P need not be multiples of the tile (a tile never crosses a column block).  Everything
- * else (phases, comm_cus, status, timeout_us, errors) as pk_gemm_rs.
+ * else (phases without PK_PHASE_OVERLAP, comm_cus, status, timeout_us, errors) as pk_gemm_rs.
  */
 pk_status pk_gemm_rs_cols_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
 pk_status pk_gemm_rs_cols(int P, int rank, int64_t M, int64_t N, int64_t K, pk_dtype dt,
@@ -221,6 +221,7 @@ pk_status pk_gemm_rs_cols(int P, int rank, int64_t M, int64_t N, int64_t K, pk_d
  *
  * phases: PK_PHASE_GEMM | PK_PHASE_REDUCE as pk_gemm_rs; PK_PHASE_WAIT adds a kernel that waits (bounded) until all
  * of ar_flags_in has reached `epoch`, so that work queued behind this call on `stream` may read all of out_full.
+ * PK_PHASE_OVERLAP is not built for this call (PK_ERR_ARG).
  * Shape requirements, comm_cus, partial_dt, status and timeout_us as pk_gemm_rs.
  */
 pk_status pk_gemm_ar_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);
