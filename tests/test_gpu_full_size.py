@@ -37,12 +37,16 @@ def sample_rows(M, P, tile_m, seed, extra=24):
     return np.array(sorted(rows), dtype=np.int64)
 
 
+@pytest.mark.parametrize("overlap", [False, True], ids=["reduce_after_gemm", "reduce_beside_gemm"])
 @pytest.mark.parametrize("name,rank", [("cfg3", 0), ("cfg3", 7), ("cfg5", 3)])
-def test_gemm_rs_full_size_sampled_rows(name, rank):
+def test_gemm_rs_full_size_sampled_rows(name, rank, overlap):
+    """overlap: the call as bench.py's timed step makes it (PK_PHASE_OVERLAP: two GEMM launches, the reduce beside the
+    second; cfg5: the narrow reduce kernel next to the fp8 GEMM)."""
     c = wl.CONFIGS[name]
     inp = wl.gemm_rs_inputs(c.P, c.M, c.N, c.K, c.dtype, rank, seed=1, order=c.order)
     res = hz.run_gemm_rs(c.P, rank, c.M, c.N, c.K, c.dtype, inp["A_local"], inp["B_local"], inp["partials"],
-                         inp["scale_a"], inp["scale_b"], epoch=11, lazy=True)
+                         inp["scale_a"], inp["scale_b"], epoch=11, lazy=True,
+                         phases=pk.PHASE_ALL | (pk.PHASE_OVERLAP if overlap else 0))
     plan = res["plan"]
     assert (plan.tile_m, plan.tile_n) == (256, 256)
     assert res["status"][0] == 0
