@@ -556,10 +556,10 @@ def more_measurements(pk, wl, torch, np, L):
             pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part5, outg5, fin5, fout5, ep[0], out5,
                           phases, status)
         return f
-    t5s = timeit(rs5(pk.PHASE_ALL), n=10, w=4)
-    t5 = timeit(rs5(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=10, w=4)
-    t5g = timeit(rs5(pk.PHASE_GEMM), n=10, w=4)
-    t5r = timeit(rs5(pk.PHASE_REDUCE), n=10, w=4)
+    t5s = timeit(rs5(pk.PHASE_ALL), n=10, w=20)
+    t5 = timeit(rs5(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=10, w=20)
+    t5g = timeit(rs5(pk.PHASE_GEMM), n=10, w=20)
+    t5r = timeit(rs5(pk.PHASE_REDUCE), n=10, w=20)
     bytes5 = 2 * c5.M * k5 + 2 * c5.M * c5.N * 4 + mp5 * c5.N * 2
     red5 = c5.M * c5.N * 4 + mp5 * c5.N * 2
     out["cfg5_fp8_gemm_rs"] = {
@@ -582,9 +582,9 @@ def more_measurements(pk, wl, torch, np, L):
             pk.pk_gemm_rs(c5.P, rank, c5.M, c5.N, c5.K, c5.dtype, A5, B5, sa5, sb5, part16, outg16, fin5, fout5, ep[0], out5,
                           phases, status, partial_dtype="bf16")
         return f
-    t16 = timeit(rs5_16(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=10, w=4)   # (next to the fp8 kernel: falls back to the serial reduce)
-    t16g = timeit(rs5_16(pk.PHASE_GEMM), n=10, w=4)
-    t16r = timeit(rs5_16(pk.PHASE_REDUCE), n=10, w=4)
+    t16 = timeit(rs5_16(pk.PHASE_ALL | pk.PHASE_OVERLAP), n=10, w=20)   # (next to the fp8 kernel: falls back to the serial reduce)
+    t16g = timeit(rs5_16(pk.PHASE_GEMM), n=10, w=20)
+    t16r = timeit(rs5_16(pk.PHASE_REDUCE), n=10, w=20)
     bytes16 = 2 * c5.M * k5 + 2 * c5.M * c5.N * 2 + mp5 * c5.N * 2
     out["cfg5_fp8_gemm_rs"]["bf16_partial_slots"] = {
         "ms": round(t16, 4), "TFLOP/s": round(c5.flops / (t16 * 1e-3) / 1e12, 1), "gemm_phase_ms": round(t16g, 4),
