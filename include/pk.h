@@ -160,10 +160,10 @@ const char* pk_status_str(int status);
  * there.  The reduce waits only for the own block (complete by then) and for the peers' flags, never for the second GEMM
  * launch, so either may be placed first.  Results are bit-identical to the plain call.  The flag needs both phases
  * (PK_ERR_ARG otherwise) and is ignored where it cannot help: when the own block takes every round of the schedule, and
- * next to the 256x256 fp8 kernel with bf16 slots or P other than 2, 4, 8.  Calls with the flag from several host threads
- * on one device are serialised while they enqueue.
- * comm_cus: as for pk_ag_gemm below, the
- * number of compute units the GEMM phase leaves to communicator workgroups (0 = none).  partial_dt: element type of
+ * next to the 256x256 fp8 kernel with bf16 slots, with a k-contiguous second operand, or with P other than 2, 4, 8.
+ * Calls with the flag from several host threads on one device are serialised while they enqueue.
+ * comm_cus: as for pk_ag_gemm below, the number of compute units the GEMM phase leaves to communicator workgroups
+ * (0 = none).  partial_dt: element type of
  * `partials` and `outgoing` (PK_ERR_DTYPE if unknown).
  */
 pk_status pk_gemm_rs_plan(int P, int64_t M, int64_t N, int64_t K, pk_dtype dt, pk_plan* plan /* host */);

@@ -599,11 +599,11 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     // the second part produces, so whichever of the two the hardware places first, both finish.
     bool overlap = (phases & PK_PHASE_OVERLAP) && do_gemm && do_reduce && !ar && !cols && P > 1;
     int first_rows = 0;                      // tile rows of the first part (0: one launch for everything)
-    // The 256x256 fp8 GEMM leaves 48 registers per lane beside its two waves per SIMD (32 with bf16 slots: too few), the
-    // bf16 one 96: the reduce kernel that runs next to the former is the narrow one, built for fp32 slots and P of 2, 4
-    // or 8 (otherwise no overlap there).
-    const bool narrow_reduce = fp8 && pl.tile_m == 256;
-    if (narrow_reduce && (bf16_slots || (P != 2 && P != 4 && P != 8))) overlap = false;
+    // Registers per lane that the 256x256 GEMM kernels leave beside their two waves per SIMD: bf16 96, bf16 with the second
+    // operand k-contiguous 48, fp8 48 (32 with bf16 slots, 16 with the second operand k-contiguous: too few).  Next to the
+    // ones that leave 48 the narrow reduce kernel runs, built for fp32 slots and P of 2, 4 or 8; otherwise no overlap there.
+    const bool narrow_reduce = pl.tile_m == 256 && (fp8 || bt);
+    if (narrow_reduce && (bf16_slots || (fp8 && bt) || (P != 2 && P != 4 && P != 8))) overlap = false;
     // one shard (slot): rows x cols.  Scatter along rows: M/P x N; along the last dimension: M x N/P
     const int64_t rows = cols ? M : M / P;
     const int64_t slot_cols = cols ? N / P : N;

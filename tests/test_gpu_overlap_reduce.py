@@ -105,3 +105,17 @@ def test_overlap_flag_with_a_single_rank_is_the_plain_gemm():
     inp = wl.gemm_rs_inputs(1, 1024, 2048, 512, "bf16", 0, seed=4)
     res = hz.run_gemm_rs(1, 0, 1024, 2048, 512, "bf16", inp["A_local"], inp["B_local"], inp["partials"], phases=OVERLAP)
     check_rs(1, 0, "bf16", inp, res, 512)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp8"])
+def test_overlap_flag_with_a_k_contiguous_second_operand(dtype):
+    """bf16: the narrow reduce kernel beside the k-contiguous GEMM kernel; fp8: no room beside that kernel, plain order."""
+    P, rank, M, N, K = 8, 6, 8192, 4096, 8192
+    inp = wl.gemm_rs_inputs(P, M, N, K, dtype, rank, seed=13)
+    Bt = np.ascontiguousarray(inp["B_local"].T)
+    kw = dict(scale_a=inp.get("scale_a"), scale_b=inp.get("scale_b"), epoch=3)
+    plain = hz.run_gemm_rs(P, rank, M, N, K, dtype, inp["A_local"], inp["B_local"], inp["partials"], **kw)
+    over = hz.run_gemm_rs(P, rank, M, N, K, dtype, inp["A_local"], Bt, inp["partials"], phases=OVERLAP, b_layout="nk", **kw)
+    assert over["plan"].tile_m == 256
+    check_rs(P, rank, dtype, inp, over, K // P)
+    assert np.array_equal(over["out_bits"], plain["out_bits"])
