@@ -156,8 +156,8 @@ const char* pk_status_str(int status);
  * compute workers): the tile rows of this rank's own block (with as many of the following ones as fill whole rounds of
  * workgroups) are computed first, in a launch of their own; the rest of the GEMM
  * and the reduce then run side by side, the reduce on a second stream that the library keeps per device (created at the
- * first such call on a device, default priority) and joins back into `stream` before the call's work counts as done
- * there.  The reduce waits only for the own block (complete by then) and for the peers' flags, never for the second GEMM
+ * first such call on a device outside a graph capture, default priority; a call on a capturing stream before that runs
+ * in the plain order) and joins back into `stream` before the call's work counts as done there.  The reduce waits only for the own block (complete by then) and for the peers' flags, never for the second GEMM
  * launch, so either may be placed first.  Results are bit-identical to the plain call.  The flag needs both phases
  * (PK_ERR_ARG otherwise) and is ignored where it cannot help: when the own block takes every round of the schedule, and
  * next to the 256x256 fp8 kernel with bf16 slots, with a k-contiguous second operand, or with P other than 2, 4, 8.

@@ -604,6 +604,18 @@ static pk_status gemm_rs_impl(int P, int rank, int64_t M, int64_t N, int64_t K, 
     // ones that leave 48 the narrow reduce kernel runs, built for fp32 slots and P of 2, 4 or 8; otherwise no overlap there.
     const bool narrow_reduce = pl.tile_m == 256 && (fp8 || bt);
     if (narrow_reduce && (bf16_slots || (fp8 && bt) || (P != 2 && P != 4 && P != 8))) overlap = false;
+    if (overlap) {
+        // a stream that is being captured into a graph takes the second stream along only if that one exists already
+        // (it is created by the first eager call with the flag): no stream is created in the middle of a capture
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cap) != hipSuccess) return PK_ERR_HIP;
+        if (cap != hipStreamCaptureStatusNone) {
+            std::lock_guard<std::mutex> guard(side_lock);
+            int dev = 0;
+            if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PK_ERR_HIP;
+            if (!side_streams[dev].ready) overlap = false;
+        }
+    }
     // one shard (slot): rows x cols.  Scatter along rows: M/P x N; along the last dimension: M x N/P
     const int64_t rows = cols ? M : M / P;
     const int64_t slot_cols = cols ? N / P : N;
