@@ -382,7 +382,7 @@ def more_measurements(pk, wl, torch, np, L):
     # --- cfg3: GEMM alone (same kernel, bf16 output, no flags) against GEMM + reduce-scatter, as the paper's Table 3 ---
     m, n, k = c3.local_mnk
     Cg = torch.zeros((m, n), dtype=torch.int16, device="cuda")
-    t_gemm = timeit(lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", L["A3"], L["B3"], None, None, None, 1, Cg, status))
+    t_gemm = timeit(lambda: pk.pk_ag_gemm(1, 0, m, n, k, "bf16", L["A3"], L["B3"], None, None, None, 1, Cg, status), w=30)
 
     def fused(phases):
         def f():
@@ -390,14 +390,32 @@ def more_measurements(pk, wl, torch, np, L):
             pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, L["part"], L["outgoing"],
                           L["flags_in"], L["flags_out"], ep[0], L["out3"], phases, status)
         return f
-    t_serial = timeit(fused(pk.PHASE_ALL))
-    t_fused = timeit(fused(pk.PHASE_ALL | pk.PHASE_OVERLAP))
+    t_serial = timeit(fused(pk.PHASE_ALL), w=30)
+    t_fused = timeit(fused(pk.PHASE_ALL | pk.PHASE_OVERLAP), w=30)
     out["table3_style_cfg3"] = {"t_gemm_ms": round(t_gemm, 4), "t_fused_ms": round(t_fused, 4),
                                 "comm_ratio": round((t_fused - t_gemm) / t_fused, 4),
                                 "gemm_TFLOP/s": round(c3.flops / (t_gemm * 1e-3) / 1e12, 1),
                                 "fused_TFLOP/s": round(c3.flops / (t_fused * 1e-3) / 1e12, 1),
                                 "t_fused_serial_reduce_ms": round(t_serial, 4),
                                 "comm_ratio_serial_reduce": round((t_serial - t_gemm) / t_serial, 4)}
+    # the same with bf16 partial slots (the paper's element size for communicated tiles, s = 2 in its cost model)
+    part16 = L["part"].to(torch.bfloat16).view(torch.int16)
+    outg16 = torch.empty(part16.shape, dtype=torch.int16, device="cuda")
+
+    def fused16(phases):
+        def f():
+            ep[0] += 1
+            pk.pk_gemm_rs(c3.P, rank, c3.M, c3.N, c3.K, c3.dtype, L["A3"], L["B3"], None, None, part16, outg16,
+                          L["flags_in"], L["flags_out"], ep[0], L["out3"], phases, status, partial_dtype="bf16")
+        return f
+    t16s = timeit(fused16(pk.PHASE_ALL), w=30)
+    t16 = timeit(fused16(pk.PHASE_ALL | pk.PHASE_OVERLAP), w=30)
+    out["table3_style_cfg3"]["bf16_partial_slots"] = {
+        "t_fused_ms": round(t16, 4), "comm_ratio": round((t16 - t_gemm) / t16, 4),
+        "fused_TFLOP/s": round(c3.flops / (t16 * 1e-3) / 1e12, 1),
+        "t_fused_serial_reduce_ms": round(t16s, 4), "comm_ratio_serial_reduce": round((t16s - t_gemm) / t16s, 4)}
+    fused(pk.PHASE_ALL | pk.PHASE_OVERLAP)()          # leaves the fp32-slot result in out3 for the parity check of this run
+    del part16, outg16
     del Cg
 
     # --- variants of the two GEMM kernels, each timed alone back to back on the same buffers ---
